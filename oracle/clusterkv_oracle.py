@@ -1,0 +1,291 @@
+"""CPU oracle for the ClusterKV hot path -- TEST INFRASTRUCTURE, not product code.
+
+A plain, slow, fp64 NumPy statement of what the path computes, written from the
+paper: cosine K-means over the keys of one KV head (Section III-B), scoring of
+the query against the cluster centroids and selection of clusters in score order
+up to a token budget (Section III-C), generation of the selected token indices
+from the clustering metadata (Section IV-C, Fig. 8) and softmax attention over
+only the selected keys and values (Section II-B).  Only tests, the smoke check
+and the benchmark's CPU-baseline leg may import it; it shares no code with the
+GPU library and must never serve as a fallback for it.
+
+Everything here works on ONE head-problem (one sequence, one KV head):
+keys/values are [N, d] float64 arrays that hold exactly the values the GPU
+stores (bf16 or fp32 bit patterns widened to fp64), queries are [G, d] for the
+G query heads that share the KV head.
+
+Readings taken where the paper is silent (each is listed in the design notes):
+  * centroid = arithmetic mean of the raw (un-normalised) member keys; the
+    assignment step compares keys with the unit-length copy of each centroid,
+    rounded to the storage type of the centroid table;
+  * an empty cluster keeps its previous centroid and stays in the table;
+  * ties (equal similarity, equal score) go to the lower cluster id;
+  * a fixed iteration count replaces the run-to-convergence loop;
+  * cluster score = sum over the G query heads of <q_g, centroid>, no 1/sqrt(d);
+  * budget: WHOLE keeps the longest prefix of the score order whose sizes sum to
+    at most B; TRIM_LAST (the paper's rule) extends the prefix until the sum
+    reaches B and cuts the last cluster, keeping its trailing entries.
+
+Pin status: every function below is pinned by tests/test_oracle_*.py (worked
+example of Fig. 8, closed forms, invariants, library cross-checks, loop-only
+brute force).  The 10-iteration K-means trajectory as a whole has no printed
+values to compare with: "parity unpinned" for `kmeans` beyond its per-step pins.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+
+import numpy as np
+
+WHOLE = 0
+TRIM_LAST = 1
+
+
+# --------------------------------------------------------------------------
+# storage rounding
+# --------------------------------------------------------------------------
+def round_to_bf16(x):
+    """Nearest bf16 value (8 significant bits, ties to even), returned as fp64.
+    Assumes the bf16 normal range."""
+    x = np.asarray(x, dtype=np.float64)
+    m, e = np.frexp(x)                       # x = m * 2**e, 0.5 <= |m| < 1
+    return np.ldexp(np.rint(m * 256.0) / 256.0, e)
+
+
+def round_to_f32(x):
+    return np.asarray(x, dtype=np.float64).astype(np.float32).astype(np.float64)
+
+
+def storage_round(x, storage: str):
+    if storage == "bf16":
+        return round_to_bf16(x)
+    if storage == "f32":
+        return round_to_f32(x)
+    if storage == "f64":
+        return np.asarray(x, dtype=np.float64)
+    raise ValueError(storage)
+
+
+# --------------------------------------------------------------------------
+# K-means (Section III-B)
+# --------------------------------------------------------------------------
+def unit_rows(mu):
+    """mu_hat_c = mu_c / |mu_c| (zero rows stay zero)."""
+    mu = np.asarray(mu, dtype=np.float64)
+    n = np.sqrt((mu * mu).sum(axis=1, keepdims=True))
+    out = np.zeros_like(mu)
+    np.divide(mu, n, out=out, where=n > 0)
+    return out
+
+
+def assign(keys, mu_hat):
+    """Assignment step: label_i = argmax_c <k_i, mu_hat_c> (the key's own length
+    does not change the argmax of the cosine).  Returns (labels, best, gap) where
+    gap is best minus runner-up similarity in cosine units (inf if C == 1)."""
+    sim = keys @ mu_hat.T                                     # [N, C]
+    labels = np.argmax(sim, axis=1)                           # first maximum wins
+    best = sim[np.arange(len(keys)), labels]
+    if sim.shape[1] > 1:
+        part = np.partition(sim, -2, axis=1)
+        second = part[:, -2]
+        knorm = np.sqrt((keys * keys).sum(axis=1))
+        gap = np.where(knorm > 0, (best - second) / np.where(knorm > 0, knorm, 1.0), 0.0)
+    else:
+        gap = np.full(len(keys), np.inf)
+    return labels.astype(np.int64), best, gap
+
+
+def update(keys, labels, mu_prev):
+    """Update step: centroid = mean of the keys assigned to it; an empty cluster
+    keeps mu_prev.  Returns (mu, sizes)."""
+    C = mu_prev.shape[0]
+    mu = np.array(mu_prev, dtype=np.float64, copy=True)
+    sizes = np.zeros(C, dtype=np.int64)
+    for c in range(C):
+        members = keys[labels == c]
+        sizes[c] = len(members)
+        if len(members):
+            mu[c] = members.sum(axis=0) / len(members)
+    return mu, sizes
+
+
+def weighted_objective(keys, mu_hat, labels):
+    """J = sum_i |k_i| * (1 - cos(k_i, mu_hat_label_i)) = sum_i (|k_i| - <k_i, u_i>)
+    for unit-length mu_hat; the quantity both K-means steps cannot increase."""
+    knorm = np.sqrt((keys * keys).sum(axis=1))
+    return float((knorm - (keys * mu_hat[labels]).sum(axis=1)).sum())
+
+
+def cosine_objective(keys, mu_hat, labels):
+    """Plain sum of the paper's distance D = 1 - cos(k_i, centroid)."""
+    knorm = np.sqrt((keys * keys).sum(axis=1))
+    dots = (keys * mu_hat[labels]).sum(axis=1)
+    un = np.sqrt((mu_hat[labels] ** 2).sum(axis=1))
+    den = knorm * un
+    cos = np.divide(dots, den, out=np.zeros_like(dots), where=den > 0)
+    return float((1.0 - cos).sum())
+
+
+@dataclass
+class KMeansTrace:
+    """State of every iteration, so a GPU step can be checked with the oracle's
+    own inputs to that step."""
+    mu_hat: list = field(default_factory=list)    # table the t-th assignment read
+    labels: list = field(default_factory=list)    # result of the t-th assignment
+    gap: list = field(default_factory=list)       # near-tie measure per key
+    mu: list = field(default_factory=list)        # fp64 centroids after the t-th update
+    sizes: list = field(default_factory=list)
+    J: list = field(default_factory=list)         # weighted objective after assignment t
+    D: list = field(default_factory=list)         # cosine objective after assignment t
+
+
+def kmeans(keys, init_idx, n_iter, storage="bf16"):
+    """Cosine K-means of `keys` [N, d] with initial centroids keys[init_idx].
+    Returns (mu, labels, sizes, trace): fp64 centroids after the last update,
+    labels of the last assignment, cluster sizes, per-iteration trace."""
+    init_idx = np.asarray(init_idx, dtype=np.int64)
+    rows = keys[init_idx]
+    if len({r.tobytes() for r in rows}) != len(rows):
+        raise ValueError("initial centroids must be distinct key rows")
+    mu = np.array(rows, dtype=np.float64, copy=True)
+    sizes = np.zeros(len(init_idx), dtype=np.int64)
+    labels = np.zeros(len(keys), dtype=np.int64)
+    tr = KMeansTrace()
+    for _ in range(n_iter):
+        mu_hat = storage_round(unit_rows(mu), storage)
+        labels, _, gap = assign(keys, mu_hat)
+        tr.mu_hat.append(mu_hat)
+        tr.labels.append(labels)
+        tr.gap.append(gap)
+        tr.J.append(weighted_objective(keys, mu_hat, labels))
+        tr.D.append(cosine_objective(keys, mu_hat, labels))
+        mu, sizes = update(keys, labels, mu)
+        tr.mu.append(mu)
+        tr.sizes.append(sizes)
+    return mu, labels, sizes, tr
+
+
+# --------------------------------------------------------------------------
+# clustering metadata (Section IV-C, Fig. 8)
+# --------------------------------------------------------------------------
+def build_metadata(labels, C, tok_begin=0):
+    """sizes[c], offsets (exclusive prefix sum of sizes, C+1 entries) and
+    sorted_idx = token ids ordered by label, ascending token id inside a cluster.
+    labels[i] belongs to token tok_begin + i."""
+    labels = np.asarray(labels, dtype=np.int64)
+    sizes = np.bincount(labels, minlength=C).astype(np.int64)
+    offsets = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    sorted_idx = (np.argsort(labels, kind="stable") + tok_begin).astype(np.int64)
+    return sizes, offsets, sorted_idx
+
+
+# --------------------------------------------------------------------------
+# selection (Section III-C) and indexing (Section IV-C)
+# --------------------------------------------------------------------------
+def score_clusters(q_group, mu):
+    """s_c = sum_g <q_g, mu_c>; q_group [G, d], mu [C, d] (stored centroids)."""
+    return (q_group @ mu.T).sum(axis=0)
+
+
+def select_clusters(scores, sizes, budget, mode=WHOLE):
+    """Clusters in descending score order (ties: lower id first) and how many of
+    them are recalled.  Returns (order[C], n_sel_clusters, n_sel_tokens)."""
+    scores = np.asarray(scores, dtype=np.float64)
+    sizes = np.asarray(sizes, dtype=np.int64)
+    C = len(scores)
+    order = np.argsort(-scores, kind="stable")
+    cum = np.cumsum(sizes[order])
+    if mode == WHOLE:
+        n_sel = int(np.searchsorted(cum, budget, side="right"))     # cum[j-1] <= B
+        n_tok = int(cum[n_sel - 1]) if n_sel else 0
+    elif mode == TRIM_LAST:
+        j = int(np.searchsorted(cum, budget, side="left"))          # first cum >= B
+        n_sel = min(j + 1, C)
+        n_tok = int(min(cum[n_sel - 1], budget)) if n_sel else 0
+    else:
+        raise ValueError(mode)
+    return order.astype(np.int64), n_sel, n_tok
+
+
+def gather_indices(order, n_sel, offsets, sorted_idx, budget, mode=WHOLE):
+    """I_T: the sorted_idx segments of the selected clusters, concatenated in
+    selection order.  TRIM_LAST keeps the trailing entries of the last segment
+    (the slice [end - kept, end) of Fig. 8's size / end-position gather)."""
+    out = []
+    total = 0
+    for j in range(n_sel):
+        c = int(order[j])
+        beg, end = int(offsets[c]), int(offsets[c + 1])
+        if mode == TRIM_LAST and total + (end - beg) > budget:
+            beg = end - (budget - total)
+        out.append(sorted_idx[beg:end])
+        total += end - beg
+    if not out:
+        return np.zeros(0, dtype=np.int64)
+    return np.concatenate(out).astype(np.int64)
+
+
+# --------------------------------------------------------------------------
+# attention (Section II-A / II-B)
+# --------------------------------------------------------------------------
+def attention_over(q_group, K, V, token_ids, scale=None):
+    """o_g = softmax(q_g K_T^T * scale) V_T over the rows `token_ids`; empty set
+    gives zeros.  scale defaults to 1/sqrt(d)."""
+    q_group = np.asarray(q_group, dtype=np.float64)
+    d = q_group.shape[1]
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    token_ids = np.asarray(token_ids, dtype=np.int64)
+    if token_ids.size == 0:
+        return np.zeros((q_group.shape[0], V.shape[1]))
+    Ks, Vs = K[token_ids], V[token_ids]
+    logits = (q_group @ Ks.T) * scale                       # [G, n]
+    logits = logits - logits.max(axis=1, keepdims=True)
+    p = np.exp(logits)
+    p = p / p.sum(axis=1, keepdims=True)
+    return p @ Vs
+
+
+def attended_set(token_idx, n_sink=0, recent_begin=0, recent_end=0):
+    """T = [0, n_sink) + I_T + [recent_begin, recent_end): always-kept leading
+    tokens, the recalled tokens, and the newest tokens no cluster covers yet."""
+    parts = [np.arange(0, n_sink, dtype=np.int64),
+             np.asarray(token_idx, dtype=np.int64),
+             np.arange(recent_begin, max(recent_begin, recent_end), dtype=np.int64)]
+    return np.concatenate(parts)
+
+
+def sparse_attention(q_group, K, V, token_idx, n_sink=0, recent_begin=0, recent_end=0,
+                     scale=None):
+    return attention_over(q_group, K, V,
+                          attended_set(token_idx, n_sink, recent_begin, recent_end), scale)
+
+
+def full_attention(q_group, K, V, n_tokens=None, scale=None):
+    n = len(K) if n_tokens is None else n_tokens
+    return attention_over(q_group, K, V, np.arange(n), scale)
+
+
+# --------------------------------------------------------------------------
+# one decode step of the whole path for one head-problem
+# --------------------------------------------------------------------------
+def decode_step(q_group, K, V, mu_stored, sizes, offsets, sorted_idx, budget, mode=WHOLE,
+                n_sink=0, recent_begin=0, recent_end=0):
+    scores = score_clusters(q_group, mu_stored)
+    order, n_sel, n_tok = select_clusters(scores, sizes, budget, mode)
+    idx = gather_indices(order, n_sel, offsets, sorted_idx, budget, mode)
+    out = sparse_attention(q_group, K, V, idx, n_sink, recent_begin, recent_end)
+    return dict(scores=scores, order=order, n_sel=n_sel, n_tok=n_tok, idx=idx, out=out)
+
+
+def selection_near_tie(scores, order, n_sel, tol=1e-4):
+    """True when a pair of neighbours in the score order, at or before the
+    boundary between the last recalled and the first rejected cluster, is closer
+    than tol*(1+|s|): then a rounding difference may legitimately change the
+    recalled list."""
+    s = np.asarray(scores, dtype=np.float64)[order]
+    hi = min(n_sel, len(s) - 1)
+    for j in range(hi):
+        if abs(s[j] - s[j + 1]) < tol * (1.0 + abs(s[j])):
+            return True
+    return False
