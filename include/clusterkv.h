@@ -1,0 +1,223 @@
+/*
+ * clusterkv.h -- C ABI of the MI355X (gfx950) ClusterKV hot-path library.
+ *
+ * The library implements the data-parallel hot path of ClusterKV: cosine
+ * K-means over the keys of every KV head (paper Section III-B), and per decode
+ * step the scoring of the query against the cluster centroids, the selection of
+ * clusters in score order up to a token budget (Section III-C), the generation
+ * of the selected token indices from the clustering metadata (Section IV-C,
+ * Fig. 8) and GQA decode attention over only the recalled keys/values
+ * (Section II-B).
+ *
+ * Conventions that hold for every call
+ * ------------------------------------
+ *  - Pointers marked [dev] are device (HBM) pointers, [host] are host pointers.
+ *    All device buffers are allocated, owned and freed by the caller; the
+ *    library allocates no device memory and keeps no state between calls.
+ *  - A "head-problem" is one (sequence s, KV head h) pair, linear index
+ *    hp = s * Hkv + h.  Query head hq belongs to KV head hq / (Hq / Hkv).
+ *  - All tensors are row-major with the last dimension contiguous:
+ *      K, V        [S, Hkv, N_cap, d]      storage type (bf16 or fp32)
+ *      q, out      [S, Hq, d]              storage type
+ *      centroids   [S, Hkv, C_cap, d]      storage type (arithmetic mean of member keys)
+ *      labels      [S, Hkv, N_cap]         int32, cluster id of every clustered token
+ *      sizes       [S, Hkv, C_cap]         int32
+ *      offsets     [S, Hkv, C_cap + 1]     int32, positions into sorted_idx;
+ *                                          cluster c owns [offsets[c], offsets[c+1])
+ *      sorted_idx  [S, Hkv, N_cap]         int32, token rows ordered by cluster id,
+ *                                          ascending token row inside a cluster
+ *    Device pointers must be 16-byte aligned.
+ *  - Every call only enqueues work on `stream` (a hipStream_t passed as void*,
+ *    NULL = the default stream) and returns; nothing synchronises the device.
+ *  - Return value: CK_OK (0) or a negative CK_E* code.  Arguments are validated
+ *    on the host before anything is enqueued; on error nothing is enqueued and
+ *    no output is touched.  ck_strerror() names a code; ck_last_error_detail()
+ *    gives the text of the last failure on the calling thread.
+ *  - Integer outputs are bit-reproducible from run to run.  Floating-point
+ *    outputs are too (no floating-point atomics are used anywhere).
+ *  - Supported: d == 128; Hq / Hkv in {1, 2, 4, 8}; cluster counts up to
+ *    CK_MAX_CLUSTERS per head-problem.
+ */
+#ifndef CLUSTERKV_H
+#define CLUSTERKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CK_VERSION 100
+
+#define CK_OK 0
+#define CK_EINVALID (-1)      /* null pointer, non-positive size, inconsistent range */
+#define CK_EUNSUPPORTED (-2)  /* shape or type outside what the kernels handle */
+#define CK_EWORKSPACE (-3)    /* workspace missing or too small */
+#define CK_EMISALIGNED (-4)   /* a device pointer is not 16-byte aligned */
+#define CK_EHIP (-5)          /* the HIP runtime reported an error at launch */
+
+#define CK_BF16 0             /* storage type of q, K, V, centroids, out */
+#define CK_F32 1              /* fp32 check mode (decode-step calls only) */
+
+#define CK_SEL_WHOLE 0u       /* recall only whole clusters: token count <= budget */
+#define CK_SEL_TRIM_LAST 1u   /* paper's rule: fill the budget, trimming the last cluster */
+
+#define CK_MAX_CLUSTERS 2048
+
+/* which = argument of ck_workspace_bytes */
+#define CK_WS_CLUSTER_KEYS 0
+#define CK_WS_SPARSE_ATTN 1
+
+typedef struct ck_shape {
+  int32_t S;       /* sequences in the batch */
+  int32_t Hq;      /* query heads */
+  int32_t Hkv;     /* KV heads */
+  int32_t d;       /* head dimension, must be 128 */
+  int64_t N_cap;   /* token rows per head-problem in K, V, labels, sorted_idx */
+  int32_t C_cap;   /* rows per head-problem in centroids and sizes (offsets has C_cap + 1) */
+  int32_t dtype;   /* CK_BF16 or CK_F32 */
+} ck_shape;
+
+int ck_version(void);
+const char* ck_strerror(int code);
+const char* ck_last_error_detail(void);
+
+/*
+ * Bytes of device scratch a call needs.
+ *   CK_WS_CLUSTER_KEYS: n = number of tokens clustered per head-problem
+ *                       (tok_count), c = number of clusters (c_count).
+ *   CK_WS_SPARSE_ATTN:  n = upper bound of attended tokens per head-problem
+ *                       (budget + n_sink + recent window), c ignored.
+ * Returns 0 for an invalid request.
+ */
+size_t ck_workspace_bytes(const ck_shape* sh, int which, int64_t n, int32_t c);
+
+/*
+ * Semantic clustering (Section III-B): cosine K-means with a fixed iteration
+ * count over tokens [tok_begin, tok_begin + tok_count) of every head-problem,
+ * producing clusters [c_begin, c_begin + c_count) and their metadata
+ * (Section IV-C: sizes, prefix sum, label-sorted token index).
+ *
+ *   prefill:      tok_begin = n_sink, tok_count = N - n_sink, c_begin = 0, c_count = C0
+ *   incremental:  tok_begin = first generated token not yet clustered, tok_count = m,
+ *                 c_begin = clusters present so far, c_count = C+   (Section III-B, last part)
+ *
+ * K          [dev] keys, CK_BF16 only.
+ * init_idx   [dev] int32 [S, Hkv, c_count]: absolute token rows whose keys are the
+ *            initial centroids ("randomly sample key vectors"); the caller draws them.
+ * n_iter     >= 1 iterations of {assignment by largest cosine similarity; update =
+ *            mean of the assigned keys}.  An empty cluster keeps its previous
+ *            centroid and size 0.  Ties go to the lower cluster id.
+ * centroids  [dev] out: rows [c_begin, c_begin + c_count) of every head-problem.
+ * labels     [dev] out: entries [tok_begin, tok_begin + tok_count), global cluster ids.
+ * sizes      [dev] out: entries [c_begin, c_begin + c_count).
+ * offsets    [dev] in/out: entries (c_begin, c_begin + c_count] are written;
+ *            offsets[c_begin] is written as 0 when c_begin == 0 and otherwise read
+ *            (it must hold the end of the previous clusters' segment).
+ * sorted_idx [dev] out: positions [offsets[c_begin], offsets[c_begin] + tok_count).
+ * workspace  [dev] scratch of ck_workspace_bytes(sh, CK_WS_CLUSTER_KEYS, tok_count, c_count).
+ * Errors: CK_EINVALID (null, tok range outside [0, N_cap], c range outside [0, C_cap],
+ *   c_count > tok_count, n_iter < 1), CK_EUNSUPPORTED (dtype != CK_BF16, d != 128,
+ *   c_count > CK_MAX_CLUSTERS), CK_EWORKSPACE, CK_EMISALIGNED, CK_EHIP.
+ */
+int ck_cluster_keys(const ck_shape* sh, const void* K, int64_t tok_begin, int64_t tok_count,
+                    int32_t c_begin, int32_t c_count, int32_t n_iter, const int32_t* init_idx,
+                    void* centroids, int32_t* labels, int32_t* sizes, int32_t* offsets,
+                    int32_t* sorted_idx, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The three steps ck_cluster_keys iterates, exported so that each can be checked
+ * on its own inputs (Section III-B; Section IV-C for the metadata).
+ *
+ * ck_kmeans_assign: labels[i] = c_begin + argmax_c <k_i, centroids_hat[c]> for the
+ *   tokens of the range.  centroids_hat [dev] bf16 [S, Hkv, c_count, d] holds the
+ *   unit-length copies of the centroids (dense, row stride d, head-problem stride
+ *   c_count * d).  best_sim [dev] fp32 [S, Hkv, N_cap] (nullable) receives the
+ *   winning similarity <k_i, centroid_hat> of every token of the range.
+ */
+int ck_kmeans_assign(const ck_shape* sh, const void* K, int64_t tok_begin, int64_t tok_count,
+                     const void* centroids_hat, int32_t c_begin, int32_t c_count,
+                     int32_t* labels, float* best_sim, void* stream);
+
+/*
+ * ck_build_metadata: from labels of the token range, sizes / offsets / sorted_idx
+ *   of clusters [c_begin, c_begin + c_count) (same in/out rules as ck_cluster_keys).
+ *   workspace: ck_workspace_bytes(sh, CK_WS_CLUSTER_KEYS, tok_count, c_count).
+ */
+int ck_build_metadata(const ck_shape* sh, const int32_t* labels, int64_t tok_begin,
+                      int64_t tok_count, int32_t c_begin, int32_t c_count, int32_t* sizes,
+                      int32_t* offsets, int32_t* sorted_idx, void* workspace,
+                      size_t workspace_bytes, void* stream);
+
+/*
+ * ck_kmeans_update: centroid = mean of its member keys, members taken from the
+ *   metadata (so ck_build_metadata must have run on the labels).  Writes
+ *   centroids (storage type, rows [c_begin, c_begin + c_count)), centroids_hat
+ *   (bf16, dense [S, Hkv, c_count, d], unit length) and, if not NULL,
+ *   centroids_f32 (fp32, dense [S, Hkv, c_count, d], the unrounded means).
+ *   Rows of empty clusters are left untouched in all three.
+ */
+int ck_kmeans_update(const ck_shape* sh, const void* K, const int32_t* sizes,
+                     const int32_t* offsets, const int32_t* sorted_idx, int32_t c_begin,
+                     int32_t c_count, void* centroids, void* centroids_hat,
+                     float* centroids_f32, void* stream);
+
+/*
+ * Cluster selection (Section III-C; Section IV-C up to the prefix sum): per
+ * head-problem, score every cluster as sum over the query heads of the group of
+ * <q_g, centroid_c> (inner product, no scaling), order the clusters by
+ * descending score (ties: lower id first), and count how many leading clusters
+ * are recalled under `budget`:
+ *   CK_SEL_WHOLE      the longest prefix whose sizes sum to <= budget (may be 0);
+ *   CK_SEL_TRIM_LAST  the shortest prefix whose sizes sum to >= budget (all
+ *                     clusters if the total is smaller); the last one is cut.
+ * q            [dev] [S, Hq, d].
+ * n_clusters   clusters present per head-problem (<= C_cap, <= CK_MAX_CLUSTERS).
+ * sel_clusters [dev] out int32 [S, Hkv, C_cap]: ALL n_clusters ids in score order;
+ *              the first n_sel_clusters of them are the recalled ones.
+ * n_sel_clusters, n_sel_tokens [dev] out int32 [S, Hkv].
+ * scores       [dev] out fp32 [S, Hkv, C_cap], nullable.
+ */
+int ck_select_clusters(const ck_shape* sh, const void* q, const void* centroids,
+                       const int32_t* sizes, int32_t n_clusters, int32_t budget, uint32_t flags,
+                       int32_t* sel_clusters, int32_t* n_sel_clusters, int32_t* n_sel_tokens,
+                       float* scores, void* stream);
+
+/*
+ * Index generation (Section IV-C, Fig. 8): concatenate, in selection order, the
+ * sorted_idx segments of the recalled clusters into token_idx.
+ * token_idx [dev] out int32 [S, Hkv, idx_stride], idx_stride >= budget;
+ * n_tokens  [dev] out int32 [S, Hkv].  With CK_SEL_TRIM_LAST the last cluster
+ * contributes only the trailing entries of its segment that still fit.
+ * A cluster that would overflow idx_stride is cut the same way in either mode,
+ * so the call never writes past a row.
+ */
+int ck_gather_indices(const ck_shape* sh, const int32_t* sel_clusters,
+                      const int32_t* n_sel_clusters, const int32_t* offsets,
+                      const int32_t* sorted_idx, int32_t budget, uint32_t flags,
+                      int32_t* token_idx, int32_t idx_stride, int32_t* n_tokens, void* stream);
+
+/*
+ * Sparse GQA decode attention (Section II-B): for every query head,
+ *   out = softmax(q K_T^T * softmax_scale) V_T
+ * over T = [0, n_sink) + token_idx[0 .. n_tokens) + [recent_begin, recent_end)
+ * of its KV head (the three parts are assumed disjoint; an empty T gives zeros).
+ * K and V rows are read once per KV head and shared by the query heads of the
+ * group.  Accumulation is fp32.
+ * token_idx [dev] int32 [S, Hkv, idx_stride] (nullable if n_tokens is NULL);
+ * n_tokens  [dev] int32 [S, Hkv], nullable = no recalled tokens;
+ * max_tokens  host upper bound of every n_tokens entry (e.g. the budget);
+ * workspace [dev] ck_workspace_bytes(sh, CK_WS_SPARSE_ATTN,
+ *           max_tokens + n_sink + recent_end - recent_begin, 0).
+ */
+int ck_sparse_decode_attn(const ck_shape* sh, const void* q, const void* K, const void* V,
+                          const int32_t* token_idx, const int32_t* n_tokens, int32_t idx_stride,
+                          int32_t max_tokens, int64_t n_sink, int64_t recent_begin,
+                          int64_t recent_end, float softmax_scale, void* out, void* workspace,
+                          size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CLUSTERKV_H */

@@ -1,0 +1,20 @@
+"""MI355X-native ClusterKV hot path: thin Python binding over libclusterkv.so.
+
+Every step of the path (K-means assignment/update, metadata, cluster selection,
+index gather, sparse decode attention) runs in the HIP kernels of the C-ABI
+library declared in include/clusterkv.h.  This package only marshals torch
+tensors (device memory, current stream) into those calls.  There is no CPU or
+PyTorch fallback: a missing library is an error.
+"""
+from .binding import (CK_BF16, CK_F32, CK_SEL_TRIM_LAST, CK_SEL_WHOLE, CK_MAX_CLUSTERS,
+                      ClusterKVError, ClusterState, Shape, ck_build_metadata, ck_cluster_keys,
+                      ck_gather_indices, ck_kmeans_assign, ck_kmeans_update,
+                      ck_select_clusters, ck_sparse_decode_attn, ck_version,
+                      ck_workspace_bytes, decode_step, load_library)
+
+__all__ = [
+    "CK_BF16", "CK_F32", "CK_SEL_TRIM_LAST", "CK_SEL_WHOLE", "CK_MAX_CLUSTERS",
+    "ClusterKVError", "ClusterState", "Shape", "ck_build_metadata", "ck_cluster_keys",
+    "ck_gather_indices", "ck_kmeans_assign", "ck_kmeans_update", "ck_select_clusters",
+    "ck_sparse_decode_attn", "ck_version", "ck_workspace_bytes", "decode_step", "load_library",
+]

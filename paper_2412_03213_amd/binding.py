@@ -1,0 +1,274 @@
+"""ctypes binding of libclusterkv.so: argument marshalling only.
+
+Functions carry the names of the C entry points (include/clusterkv.h) and take
+torch tensors in the layouts documented there.  Work is enqueued on torch's
+current stream; nothing here synchronises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+CK_BF16, CK_F32 = 0, 1
+CK_SEL_WHOLE, CK_SEL_TRIM_LAST = 0, 1
+CK_MAX_CLUSTERS = 2048
+CK_WS_CLUSTER_KEYS, CK_WS_SPARSE_ATTN = 0, 1
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libclusterkv.so")
+
+EXPORTS = ("ck_version", "ck_strerror", "ck_last_error_detail", "ck_workspace_bytes",
+           "ck_cluster_keys", "ck_kmeans_assign", "ck_build_metadata", "ck_kmeans_update",
+           "ck_select_clusters", "ck_gather_indices", "ck_sparse_decode_attn")
+
+
+class ClusterKVError(RuntimeError):
+    def __init__(self, code: int, name: str, detail: str):
+        super().__init__(f"{name} (code {code}): {detail}")
+        self.code = code
+
+
+class _CkShape(ctypes.Structure):
+    _fields_ = [("S", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
+                ("d", ctypes.c_int32), ("N_cap", ctypes.c_int64), ("C_cap", ctypes.c_int32),
+                ("dtype", ctypes.c_int32)]
+
+
+@dataclass(frozen=True)
+class Shape:
+    S: int
+    Hq: int
+    Hkv: int
+    N_cap: int
+    C_cap: int
+    d: int = 128
+    dtype: int = CK_BF16
+
+    def c(self) -> _CkShape:
+        return _CkShape(self.S, self.Hq, self.Hkv, self.d, self.N_cap, self.C_cap, self.dtype)
+
+    @property
+    def torch_dtype(self):
+        return torch.bfloat16 if self.dtype == CK_BF16 else torch.float32
+
+
+_lib = None
+
+
+def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
+    """Load the in-tree library; build it first only when no built library exists."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        if not build_if_missing:
+            raise RuntimeError(f"{LIB_PATH} is missing: run python -m paper_2412_03213_amd.build")
+        from .build import build
+        build(verbose=False)
+    lib = ctypes.CDLL(LIB_PATH)
+    P, I32, I64, U32, SZ, F = (ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint32,
+                               ctypes.c_size_t, ctypes.c_float)
+    SH = ctypes.POINTER(_CkShape)
+    lib.ck_version.restype = ctypes.c_int
+    lib.ck_version.argtypes = []
+    lib.ck_strerror.restype = ctypes.c_char_p
+    lib.ck_strerror.argtypes = [ctypes.c_int]
+    lib.ck_last_error_detail.restype = ctypes.c_char_p
+    lib.ck_last_error_detail.argtypes = []
+    lib.ck_workspace_bytes.restype = SZ
+    lib.ck_workspace_bytes.argtypes = [SH, ctypes.c_int, I64, I32]
+    lib.ck_cluster_keys.restype = ctypes.c_int
+    lib.ck_cluster_keys.argtypes = [SH, P, I64, I64, I32, I32, I32, P, P, P, P, P, P, P, SZ, P]
+    lib.ck_kmeans_assign.restype = ctypes.c_int
+    lib.ck_kmeans_assign.argtypes = [SH, P, I64, I64, P, I32, I32, P, P, P]
+    lib.ck_build_metadata.restype = ctypes.c_int
+    lib.ck_build_metadata.argtypes = [SH, P, I64, I64, I32, I32, P, P, P, P, SZ, P]
+    lib.ck_kmeans_update.restype = ctypes.c_int
+    lib.ck_kmeans_update.argtypes = [SH, P, P, P, P, I32, I32, P, P, P, P]
+    lib.ck_select_clusters.restype = ctypes.c_int
+    lib.ck_select_clusters.argtypes = [SH, P, P, P, I32, I32, U32, P, P, P, P, P]
+    lib.ck_gather_indices.restype = ctypes.c_int
+    lib.ck_gather_indices.argtypes = [SH, P, P, P, P, I32, U32, P, I32, P, P]
+    lib.ck_sparse_decode_attn.restype = ctypes.c_int
+    lib.ck_sparse_decode_attn.argtypes = [SH, P, P, P, P, P, I32, I32, I64, I64, I64, F, P, P,
+                                          SZ, P]
+    _lib = lib
+    return lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        lib = load_library()
+        raise ClusterKVError(rc, lib.ck_strerror(rc).decode(),
+                             lib.ck_last_error_detail().decode())
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):          # raw address (used by the argument-validation tests)
+        return t
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    return t.data_ptr()
+
+
+def _stream(t) -> int:
+    if isinstance(t, torch.Tensor) and t.is_cuda:
+        return torch.cuda.current_stream(t.device).cuda_stream
+    return 0
+
+
+def ck_version() -> int:
+    return load_library().ck_version()
+
+
+def ck_workspace_bytes(sh: Shape, which: int, n: int, c: int = 0) -> int:
+    s = sh.c()
+    return int(load_library().ck_workspace_bytes(ctypes.byref(s), which, n, c))
+
+
+def _workspace(nbytes: int, like: torch.Tensor) -> torch.Tensor:
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=like.device)
+
+
+def ck_cluster_keys(sh: Shape, K, tok_begin, tok_count, c_begin, c_count, n_iter, init_idx,
+                    centroids, labels, sizes, offsets, sorted_idx, workspace=None):
+    lib = load_library()
+    if workspace is None:
+        workspace = _workspace(ck_workspace_bytes(sh, CK_WS_CLUSTER_KEYS, tok_count, c_count), K)
+    s = sh.c()
+    _check(lib.ck_cluster_keys(ctypes.byref(s), _ptr(K), tok_begin, tok_count, c_begin, c_count,
+                               n_iter, _ptr(init_idx), _ptr(centroids), _ptr(labels),
+                               _ptr(sizes), _ptr(offsets), _ptr(sorted_idx), _ptr(workspace),
+                               workspace.numel() if isinstance(workspace, torch.Tensor) else 0,
+                               _stream(K)))
+    return workspace
+
+
+def ck_kmeans_assign(sh: Shape, K, tok_begin, tok_count, centroids_hat, c_begin, c_count, labels,
+                     best_sim=None):
+    lib = load_library()
+    s = sh.c()
+    _check(lib.ck_kmeans_assign(ctypes.byref(s), _ptr(K), tok_begin, tok_count,
+                                _ptr(centroids_hat), c_begin, c_count, _ptr(labels),
+                                _ptr(best_sim), _stream(K)))
+
+
+def ck_build_metadata(sh: Shape, labels, tok_begin, tok_count, c_begin, c_count, sizes, offsets,
+                      sorted_idx, workspace=None):
+    lib = load_library()
+    if workspace is None:
+        workspace = _workspace(ck_workspace_bytes(sh, CK_WS_CLUSTER_KEYS, tok_count, c_count),
+                               labels)
+    s = sh.c()
+    _check(lib.ck_build_metadata(ctypes.byref(s), _ptr(labels), tok_begin, tok_count, c_begin,
+                                 c_count, _ptr(sizes), _ptr(offsets), _ptr(sorted_idx),
+                                 _ptr(workspace),
+                                 workspace.numel() if isinstance(workspace, torch.Tensor) else 0,
+                                 _stream(labels)))
+    return workspace
+
+
+def ck_kmeans_update(sh: Shape, K, sizes, offsets, sorted_idx, c_begin, c_count, centroids,
+                     centroids_hat, centroids_f32=None):
+    lib = load_library()
+    s = sh.c()
+    _check(lib.ck_kmeans_update(ctypes.byref(s), _ptr(K), _ptr(sizes), _ptr(offsets),
+                                _ptr(sorted_idx), c_begin, c_count, _ptr(centroids),
+                                _ptr(centroids_hat), _ptr(centroids_f32), _stream(K)))
+
+
+def ck_select_clusters(sh: Shape, q, centroids, sizes, n_clusters, budget, flags, sel_clusters,
+                       n_sel_clusters, n_sel_tokens, scores=None):
+    lib = load_library()
+    s = sh.c()
+    _check(lib.ck_select_clusters(ctypes.byref(s), _ptr(q), _ptr(centroids), _ptr(sizes),
+                                  n_clusters, budget, flags, _ptr(sel_clusters),
+                                  _ptr(n_sel_clusters), _ptr(n_sel_tokens), _ptr(scores),
+                                  _stream(q)))
+
+
+def ck_gather_indices(sh: Shape, sel_clusters, n_sel_clusters, offsets, sorted_idx, budget, flags,
+                      token_idx, n_tokens):
+    lib = load_library()
+    s = sh.c()
+    stride = token_idx.shape[-1] if isinstance(token_idx, torch.Tensor) else budget
+    _check(lib.ck_gather_indices(ctypes.byref(s), _ptr(sel_clusters), _ptr(n_sel_clusters),
+                                 _ptr(offsets), _ptr(sorted_idx), budget, flags, _ptr(token_idx),
+                                 stride, _ptr(n_tokens), _stream(sel_clusters)))
+
+
+def ck_sparse_decode_attn(sh: Shape, q, K, V, token_idx, n_tokens, max_tokens, out, n_sink=0,
+                          recent_begin=0, recent_end=0, softmax_scale=None, workspace=None):
+    lib = load_library()
+    if softmax_scale is None:
+        softmax_scale = sh.d ** -0.5
+    n_recent = max(0, recent_end - recent_begin)
+    if workspace is None:
+        workspace = _workspace(
+            ck_workspace_bytes(sh, CK_WS_SPARSE_ATTN, max_tokens + n_sink + n_recent), q)
+    stride = token_idx.shape[-1] if isinstance(token_idx, torch.Tensor) else 0
+    s = sh.c()
+    _check(lib.ck_sparse_decode_attn(ctypes.byref(s), _ptr(q), _ptr(K), _ptr(V), _ptr(token_idx),
+                                     _ptr(n_tokens), stride, max_tokens, n_sink, recent_begin,
+                                     recent_end, softmax_scale, _ptr(out), _ptr(workspace),
+                                     workspace.numel() if isinstance(workspace, torch.Tensor)
+                                     else 0, _stream(q)))
+    return workspace
+
+
+class ClusterState:
+    """Device buffers of one layer's clustering result (centroid table + metadata)
+    plus the per-step outputs of the decode calls, allocated once."""
+
+    def __init__(self, sh: Shape, device, budget: int, idx_stride: int | None = None,
+                 max_recent: int = 0, n_sink: int = 0):
+        self.sh = sh
+        S, H, N, C = sh.S, sh.Hkv, sh.N_cap, sh.C_cap
+        i32 = dict(dtype=torch.int32, device=device)
+        self.centroids = torch.zeros(S, H, C, sh.d, dtype=sh.torch_dtype, device=device)
+        self.labels = torch.zeros(S, H, N, **i32)
+        self.sizes = torch.zeros(S, H, C, **i32)
+        self.offsets = torch.zeros(S, H, C + 1, **i32)
+        self.sorted_idx = torch.zeros(S, H, N, **i32)
+        self.n_clusters = 0
+        self.budget = budget
+        stride = idx_stride or ((budget + 3) // 4 * 4)
+        self.sel_clusters = torch.zeros(S, H, C, **i32)
+        self.n_sel_clusters = torch.zeros(S, H, **i32)
+        self.n_sel_tokens = torch.zeros(S, H, **i32)
+        self.token_idx = torch.zeros(S, H, stride, **i32)
+        self.n_tokens = torch.zeros(S, H, **i32)
+        self.out = torch.zeros(S, sh.Hq, sh.d, dtype=sh.torch_dtype, device=device)
+        self.attn_ws = _workspace(
+            ck_workspace_bytes(sh, CK_WS_SPARSE_ATTN, budget + n_sink + max_recent),
+            self.centroids)
+        self.cluster_ws = None
+
+    def cluster(self, K, init_idx, tok_begin, tok_count, c_count, n_iter):
+        need = ck_workspace_bytes(self.sh, CK_WS_CLUSTER_KEYS, tok_count, c_count)
+        if self.cluster_ws is None or self.cluster_ws.numel() < need:
+            self.cluster_ws = _workspace(need, K)
+        ck_cluster_keys(self.sh, K, tok_begin, tok_count, self.n_clusters, c_count, n_iter,
+                        init_idx, self.centroids, self.labels, self.sizes, self.offsets,
+                        self.sorted_idx, self.cluster_ws)
+        self.n_clusters += c_count
+
+
+def decode_step(st: ClusterState, q, K, V, flags=CK_SEL_WHOLE, n_sink=0, recent_begin=0,
+                recent_end=0, scores=None):
+    """One decode step of the path: selection, index gather, sparse attention
+    (three library calls on the current stream).  Returns st.out."""
+    sh = st.sh
+    ck_select_clusters(sh, q, st.centroids, st.sizes, st.n_clusters, st.budget, flags,
+                       st.sel_clusters, st.n_sel_clusters, st.n_sel_tokens, scores)
+    ck_gather_indices(sh, st.sel_clusters, st.n_sel_clusters, st.offsets, st.sorted_idx,
+                      st.budget, flags, st.token_idx, st.n_tokens)
+    ck_sparse_decode_attn(sh, q, K, V, st.token_idx, st.n_tokens, st.budget, st.out,
+                          n_sink=n_sink, recent_begin=recent_begin, recent_end=recent_end,
+                          workspace=st.attn_ws)
+    return st.out

@@ -1,0 +1,309 @@
+// C ABI of the ClusterKV library: argument validation (host only, before anything
+// is enqueued) and the sequence of kernel launches behind every entry point.
+#include <stdarg.h>
+#include <stdio.h>
+
+#include "ck_common.hpp"
+
+namespace {
+
+thread_local char g_detail[256] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_detail, sizeof(g_detail), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+#define CK_REQUIRE_PTR(p)                                          \
+  do {                                                             \
+    if (!(p)) return fail(CK_EINVALID, "%s is NULL", #p);          \
+    if (!aligned16(p)) return fail(CK_EMISALIGNED, "%s is not 16-byte aligned", #p); \
+  } while (0)
+#define CK_OPTIONAL_PTR(p)                                         \
+  do {                                                             \
+    if ((p) && !aligned16(p)) return fail(CK_EMISALIGNED, "%s is not 16-byte aligned", #p); \
+  } while (0)
+
+int check_shape(const ck_shape* sh, ck::Dims* dm, bool need_bf16) {
+  if (!sh) return fail(CK_EINVALID, "shape is NULL");
+  if (sh->S < 1 || sh->Hq < 1 || sh->Hkv < 1 || sh->N_cap < 1 || sh->C_cap < 1)
+    return fail(CK_EINVALID, "S, Hq, Hkv, N_cap and C_cap must be positive");
+  if (sh->d != ck::D) return fail(CK_EUNSUPPORTED, "head dimension %d (only 128)", sh->d);
+  if (sh->Hq % sh->Hkv != 0)
+    return fail(CK_EINVALID, "Hq=%d is not a multiple of Hkv=%d", sh->Hq, sh->Hkv);
+  const int G = sh->Hq / sh->Hkv;
+  if (G != 1 && G != 2 && G != 4 && G != 8)
+    return fail(CK_EUNSUPPORTED, "GQA group size %d (only 1, 2, 4, 8)", G);
+  if (sh->dtype != CK_BF16 && sh->dtype != CK_F32)
+    return fail(CK_EINVALID, "unknown dtype %d", sh->dtype);
+  if (need_bf16 && sh->dtype != CK_BF16)
+    return fail(CK_EUNSUPPORTED, "clustering runs on bf16 keys only");
+  if (sh->N_cap > (int64_t)0x7FFFFFFF) return fail(CK_EUNSUPPORTED, "N_cap exceeds int32 rows");
+  if ((int64_t)sh->S * sh->Hkv > 65535)
+    return fail(CK_EUNSUPPORTED, "more than 65535 head-problems in one call");
+  dm->S = sh->S;
+  dm->Hq = sh->Hq;
+  dm->Hkv = sh->Hkv;
+  dm->G = G;
+  dm->HP = sh->S * sh->Hkv;
+  dm->N_cap = sh->N_cap;
+  dm->C_cap = sh->C_cap;
+  dm->dtype = sh->dtype;
+  return CK_OK;
+}
+
+int check_ranges(const ck_shape* sh, int64_t tok_begin, int64_t tok_count, int32_t c_begin,
+                 int32_t c_count) {
+  if (tok_begin < 0 || tok_count < 1 || tok_begin + tok_count > sh->N_cap)
+    return fail(CK_EINVALID, "token range [%lld, +%lld) outside [0, %lld]", (long long)tok_begin,
+                (long long)tok_count, (long long)sh->N_cap);
+  if (c_begin < 0 || c_count < 1 || (int64_t)c_begin + c_count > sh->C_cap)
+    return fail(CK_EINVALID, "cluster range [%d, +%d) outside [0, %d]", c_begin, c_count,
+                sh->C_cap);
+  if (c_count > CK_MAX_CLUSTERS)
+    return fail(CK_EUNSUPPORTED, "%d clusters (at most %d)", c_count, CK_MAX_CLUSTERS);
+  if (c_count > tok_count)
+    return fail(CK_EINVALID, "more clusters (%d) than tokens (%lld)", c_count,
+                (long long)tok_count);
+  return CK_OK;
+}
+
+int hip_result(hipError_t e, const char* what) {
+  if (e == hipSuccess) return CK_OK;
+  return fail(CK_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+}  // namespace
+
+extern "C" {
+
+int ck_version(void) { return CK_VERSION; }
+
+const char* ck_strerror(int code) {
+  switch (code) {
+    case CK_OK: return "success";
+    case CK_EINVALID: return "invalid argument";
+    case CK_EUNSUPPORTED: return "unsupported shape or type";
+    case CK_EWORKSPACE: return "workspace missing or too small";
+    case CK_EMISALIGNED: return "misaligned device pointer";
+    case CK_EHIP: return "HIP runtime error";
+    default: return "unknown error code";
+  }
+}
+
+const char* ck_last_error_detail(void) { return g_detail; }
+
+size_t ck_workspace_bytes(const ck_shape* sh, int which, int64_t n, int32_t c) {
+  ck::Dims dm;
+  if (check_shape(sh, &dm, false) != CK_OK) return 0;
+  if (which == CK_WS_CLUSTER_KEYS) {
+    if (n < 1 || c < 1 || c > CK_MAX_CLUSTERS) return 0;
+    return ck::carve_cluster_workspace(dm, n, c, nullptr).bytes;
+  }
+  if (which == CK_WS_SPARSE_ATTN) {
+    if (n < 0) return 0;
+    return ck::attn_workspace_bytes(dm, n);
+  }
+  return 0;
+}
+
+int ck_kmeans_assign(const ck_shape* sh, const void* K, int64_t tok_begin, int64_t tok_count,
+                     const void* centroids_hat, int32_t c_begin, int32_t c_count,
+                     int32_t* labels, float* best_sim, void* stream) {
+  ck::Dims dm;
+  int rc = check_shape(sh, &dm, true);
+  if (rc) return rc;
+  if ((rc = check_ranges(sh, tok_begin, tok_count, c_begin, c_count))) return rc;
+  CK_REQUIRE_PTR(K);
+  CK_REQUIRE_PTR(centroids_hat);
+  CK_REQUIRE_PTR(labels);
+  CK_OPTIONAL_PTR(best_sim);
+  return hip_result(ck::launch_assign(dm, (const ck::bf16*)K, tok_begin, tok_count,
+                                      (const ck::bf16*)centroids_hat, c_begin, c_count, labels,
+                                      best_sim, (hipStream_t)stream),
+                    "assignment launch");
+}
+
+int ck_build_metadata(const ck_shape* sh, const int32_t* labels, int64_t tok_begin,
+                      int64_t tok_count, int32_t c_begin, int32_t c_count, int32_t* sizes,
+                      int32_t* offsets, int32_t* sorted_idx, void* workspace,
+                      size_t workspace_bytes, void* stream) {
+  ck::Dims dm;
+  int rc = check_shape(sh, &dm, false);
+  if (rc) return rc;
+  if ((rc = check_ranges(sh, tok_begin, tok_count, c_begin, c_count))) return rc;
+  CK_REQUIRE_PTR(labels);
+  CK_REQUIRE_PTR(sizes);
+  CK_REQUIRE_PTR(offsets);
+  CK_REQUIRE_PTR(sorted_idx);
+  if (!workspace) return fail(CK_EWORKSPACE, "workspace is NULL");
+  if (!aligned16(workspace)) return fail(CK_EMISALIGNED, "workspace is not 16-byte aligned");
+  const ck::ClusterWorkspace ws = ck::carve_cluster_workspace(dm, tok_count, c_count, workspace);
+  if (workspace_bytes < ws.bytes)
+    return fail(CK_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, ws.bytes);
+  return hip_result(ck::launch_metadata(dm, labels, tok_begin, tok_count, c_begin, c_count, sizes,
+                                        offsets, sorted_idx, ws.chunk_hist, (hipStream_t)stream),
+                    "metadata launch");
+}
+
+int ck_kmeans_update(const ck_shape* sh, const void* K, const int32_t* sizes,
+                     const int32_t* offsets, const int32_t* sorted_idx, int32_t c_begin,
+                     int32_t c_count, void* centroids, void* centroids_hat,
+                     float* centroids_f32, void* stream) {
+  ck::Dims dm;
+  int rc = check_shape(sh, &dm, true);
+  if (rc) return rc;
+  if (c_begin < 0 || c_count < 1 || (int64_t)c_begin + c_count > sh->C_cap)
+    return fail(CK_EINVALID, "cluster range [%d, +%d) outside [0, %d]", c_begin, c_count,
+                sh->C_cap);
+  CK_REQUIRE_PTR(K);
+  CK_REQUIRE_PTR(sizes);
+  CK_REQUIRE_PTR(offsets);
+  CK_REQUIRE_PTR(sorted_idx);
+  CK_REQUIRE_PTR(centroids);
+  CK_REQUIRE_PTR(centroids_hat);
+  CK_OPTIONAL_PTR(centroids_f32);
+  return hip_result(ck::launch_update(dm, (const ck::bf16*)K, offsets, sorted_idx, c_begin,
+                                      c_count, (ck::bf16*)centroids, (ck::bf16*)centroids_hat,
+                                      centroids_f32, (hipStream_t)stream),
+                    "update launch");
+}
+
+int ck_cluster_keys(const ck_shape* sh, const void* K, int64_t tok_begin, int64_t tok_count,
+                    int32_t c_begin, int32_t c_count, int32_t n_iter, const int32_t* init_idx,
+                    void* centroids, int32_t* labels, int32_t* sizes, int32_t* offsets,
+                    int32_t* sorted_idx, void* workspace, size_t workspace_bytes, void* stream) {
+  ck::Dims dm;
+  int rc = check_shape(sh, &dm, true);
+  if (rc) return rc;
+  if ((rc = check_ranges(sh, tok_begin, tok_count, c_begin, c_count))) return rc;
+  if (n_iter < 1) return fail(CK_EINVALID, "n_iter=%d must be at least 1", n_iter);
+  CK_REQUIRE_PTR(K);
+  CK_REQUIRE_PTR(init_idx);
+  CK_REQUIRE_PTR(centroids);
+  CK_REQUIRE_PTR(labels);
+  CK_REQUIRE_PTR(sizes);
+  CK_REQUIRE_PTR(offsets);
+  CK_REQUIRE_PTR(sorted_idx);
+  if (!workspace) return fail(CK_EWORKSPACE, "workspace is NULL");
+  if (!aligned16(workspace)) return fail(CK_EMISALIGNED, "workspace is not 16-byte aligned");
+  const ck::ClusterWorkspace ws = ck::carve_cluster_workspace(dm, tok_count, c_count, workspace);
+  if (workspace_bytes < ws.bytes)
+    return fail(CK_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, ws.bytes);
+
+  hipStream_t st = (hipStream_t)stream;
+  const ck::bf16* Kb = (const ck::bf16*)K;
+  hipError_t e = ck::launch_init_centroids(dm, Kb, init_idx, c_begin, c_count,
+                                           (ck::bf16*)centroids, ws.mu_hat, st);
+  if (e != hipSuccess) return hip_result(e, "init launch");
+  for (int it = 0; it < n_iter; ++it) {
+    e = ck::launch_assign(dm, Kb, tok_begin, tok_count, ws.mu_hat, c_begin, c_count, labels,
+                          nullptr, st);
+    if (e != hipSuccess) return hip_result(e, "assignment launch");
+    e = ck::launch_metadata(dm, labels, tok_begin, tok_count, c_begin, c_count, sizes, offsets,
+                            sorted_idx, ws.chunk_hist, st);
+    if (e != hipSuccess) return hip_result(e, "metadata launch");
+    e = ck::launch_update(dm, Kb, offsets, sorted_idx, c_begin, c_count, (ck::bf16*)centroids,
+                          ws.mu_hat, nullptr, st);
+    if (e != hipSuccess) return hip_result(e, "update launch");
+  }
+  return CK_OK;
+}
+
+int ck_select_clusters(const ck_shape* sh, const void* q, const void* centroids,
+                       const int32_t* sizes, int32_t n_clusters, int32_t budget, uint32_t flags,
+                       int32_t* sel_clusters, int32_t* n_sel_clusters, int32_t* n_sel_tokens,
+                       float* scores, void* stream) {
+  ck::Dims dm;
+  int rc = check_shape(sh, &dm, false);
+  if (rc) return rc;
+  if (n_clusters < 1 || n_clusters > sh->C_cap)
+    return fail(CK_EINVALID, "n_clusters=%d outside [1, C_cap=%d]", n_clusters, sh->C_cap);
+  if (n_clusters > CK_MAX_CLUSTERS)
+    return fail(CK_EUNSUPPORTED, "%d clusters (at most %d)", n_clusters, CK_MAX_CLUSTERS);
+  if (budget < 1) return fail(CK_EINVALID, "budget=%d must be positive", budget);
+  if (flags > CK_SEL_TRIM_LAST) return fail(CK_EINVALID, "unknown flags 0x%x", flags);
+  CK_REQUIRE_PTR(q);
+  CK_REQUIRE_PTR(centroids);
+  CK_REQUIRE_PTR(sizes);
+  CK_REQUIRE_PTR(sel_clusters);
+  CK_REQUIRE_PTR(n_sel_clusters);
+  CK_REQUIRE_PTR(n_sel_tokens);
+  CK_OPTIONAL_PTR(scores);
+  return hip_result(ck::launch_select(dm, q, centroids, sizes, n_clusters, budget, flags,
+                                      sel_clusters, n_sel_clusters, n_sel_tokens, scores,
+                                      (hipStream_t)stream),
+                    "selection launch");
+}
+
+int ck_gather_indices(const ck_shape* sh, const int32_t* sel_clusters,
+                      const int32_t* n_sel_clusters, const int32_t* offsets,
+                      const int32_t* sorted_idx, int32_t budget, uint32_t flags,
+                      int32_t* token_idx, int32_t idx_stride, int32_t* n_tokens, void* stream) {
+  ck::Dims dm;
+  int rc = check_shape(sh, &dm, false);
+  if (rc) return rc;
+  if (budget < 1) return fail(CK_EINVALID, "budget=%d must be positive", budget);
+  if (idx_stride < budget)
+    return fail(CK_EINVALID, "idx_stride=%d smaller than budget=%d", idx_stride, budget);
+  if (idx_stride % 4 != 0) return fail(CK_EMISALIGNED, "idx_stride=%d not a multiple of 4", idx_stride);
+  if (flags > CK_SEL_TRIM_LAST) return fail(CK_EINVALID, "unknown flags 0x%x", flags);
+  CK_REQUIRE_PTR(sel_clusters);
+  CK_REQUIRE_PTR(n_sel_clusters);
+  CK_REQUIRE_PTR(offsets);
+  CK_REQUIRE_PTR(sorted_idx);
+  CK_REQUIRE_PTR(token_idx);
+  CK_REQUIRE_PTR(n_tokens);
+  return hip_result(ck::launch_gather(dm, sel_clusters, n_sel_clusters, offsets, sorted_idx,
+                                      budget, flags, token_idx, idx_stride, n_tokens,
+                                      (hipStream_t)stream),
+                    "gather launch");
+}
+
+int ck_sparse_decode_attn(const ck_shape* sh, const void* q, const void* K, const void* V,
+                          const int32_t* token_idx, const int32_t* n_tokens, int32_t idx_stride,
+                          int32_t max_tokens, int64_t n_sink, int64_t recent_begin,
+                          int64_t recent_end, float softmax_scale, void* out, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+  ck::Dims dm;
+  int rc = check_shape(sh, &dm, false);
+  if (rc) return rc;
+  if (n_sink < 0 || n_sink > sh->N_cap)
+    return fail(CK_EINVALID, "n_sink=%lld outside [0, N_cap]", (long long)n_sink);
+  if (recent_end < recent_begin) recent_end = recent_begin;
+  if (recent_begin < 0 || recent_end > sh->N_cap)
+    return fail(CK_EINVALID, "recent window [%lld, %lld) outside [0, N_cap]",
+                (long long)recent_begin, (long long)recent_end);
+  if (max_tokens < 0) return fail(CK_EINVALID, "max_tokens=%d is negative", max_tokens);
+  if (!n_tokens) max_tokens = 0;
+  if (n_tokens && max_tokens > 0) {
+    if (!token_idx) return fail(CK_EINVALID, "token_idx is NULL but n_tokens is given");
+    if (idx_stride < max_tokens)
+      return fail(CK_EINVALID, "idx_stride=%d smaller than max_tokens=%d", idx_stride, max_tokens);
+  }
+  if (!(softmax_scale > 0.f)) return fail(CK_EINVALID, "softmax_scale must be positive");
+  CK_REQUIRE_PTR(q);
+  CK_REQUIRE_PTR(K);
+  CK_REQUIRE_PTR(V);
+  CK_REQUIRE_PTR(out);
+  CK_OPTIONAL_PTR(token_idx);
+  CK_OPTIONAL_PTR(n_tokens);
+  const int64_t max_total = (int64_t)max_tokens + n_sink + (recent_end - recent_begin);
+  if (max_total > (int64_t)1 << 30) return fail(CK_EUNSUPPORTED, "attended set too large");
+  const size_t need = ck::attn_workspace_bytes(dm, max_total);
+  if (!workspace) return fail(CK_EWORKSPACE, "workspace is NULL");
+  if (!aligned16(workspace)) return fail(CK_EMISALIGNED, "workspace is not 16-byte aligned");
+  if (workspace_bytes < need)
+    return fail(CK_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+  return hip_result(ck::launch_sparse_attn(dm, q, K, V, token_idx, n_tokens, idx_stride,
+                                           max_total, n_sink, recent_begin, recent_end,
+                                           softmax_scale, out, workspace, (hipStream_t)stream),
+                    "attention launch");
+}
+
+}  // extern "C"

@@ -1,0 +1,412 @@
+"""GPU parity: every C-ABI entry point against the CPU oracle, element by element,
+on the same seeded inputs.  Integer results must be identical except where the
+oracle itself reports a near tie (top-two cosine similarity gap, or neighbouring
+cluster scores at the budget boundary, below 1e-4); attention must agree within
+2e-2 (bf16 storage, fp32 accumulation) or 1e-5 (fp32 check mode) of the largest
+output magnitude per query head.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2412_03213_amd as ck
+from ck_synth import Config, MixtureWorkload, get_config, sample_init_indices
+from oracle import clusterkv_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+NEAR_TIE = 1e-4
+ATTN_TOL = {ck.CK_BF16: 2e-2, ck.CK_F32: 1e-5}
+
+
+def np64(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def bf16_dev(a):
+    return torch.from_numpy(np.asarray(a, dtype=np.float32)).to(torch.bfloat16).to(DEV)
+
+
+def i32_dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(DEV)
+
+
+def small_cfg(N, C, M, Hkv=2, Hq=2, S=1, B=256, seed=0):
+    return Config(f"t{N}_{C}", 1, S, Hkv, Hq, 128, N, M, C, 10, B, seed)
+
+
+def rel_err(got, want):
+    """max |got - want| / max |want| per query head."""
+    den = np.maximum(np.abs(want).max(axis=-1), 1e-30)
+    return (np.abs(got - want).max(axis=-1) / den).max()
+
+
+# ---------------------------------------------------------------- K-means steps
+@pytest.mark.parametrize("N,C,M", [(2048, 32, 64), (2048 + 37, 50, 64), (3000, 400, 512),
+                                   (640, 4, 8), (96, 96, 96)])
+def test_assign_and_update_teacher_forced(N, C, M):
+    """Each GPU step gets the oracle's own input to that step."""
+    cfg = small_cfg(N, C, M)
+    w = MixtureWorkload(cfg, device=DEV)
+    init = sample_init_indices(w.K, C, cfg.seed)
+    sh = ck.Shape(cfg.S, cfg.Hq, cfg.Hkv, N, C)
+    n_iter = 3
+    flagged = total = 0
+    for h in range(cfg.Hkv):
+        keys = np64(w.K[0, h])
+        mu, labels, sizes, tr = O.kmeans(keys, init[0, h].numpy(), n_iter, storage="bf16")
+        for t in range(n_iter):
+            # --- assignment with the oracle's unit centroids of iteration t
+            mu_hat = torch.zeros(cfg.S, cfg.Hkv, C, 128, dtype=torch.bfloat16, device=DEV)
+            mu_hat[0, h] = bf16_dev(tr.mu_hat[t])
+            lab = torch.full((cfg.S, cfg.Hkv, N), -1, dtype=torch.int32, device=DEV)
+            best = torch.zeros(cfg.S, cfg.Hkv, N, dtype=torch.float32, device=DEV)
+            ck.ck_kmeans_assign(sh, w.K, 0, N, mu_hat, 0, C, lab, best)
+            got = lab[0, h].cpu().numpy()
+            near = tr.gap[t] < NEAR_TIE
+            bad = (got != tr.labels[t]) & ~near
+            assert not bad.any(), f"head {h} iter {t}: {bad.sum()} label mismatches off near-ties"
+            flagged += int(near.sum())
+            total += N
+            want_best = (keys * tr.mu_hat[t][tr.labels[t]]).sum(axis=1)
+            assert np.allclose(best[0, h].cpu().numpy()[~near], want_best[~near], rtol=1e-5,
+                               atol=1e-5)
+            # --- metadata + update from the oracle's labels of iteration t
+            lab_in = torch.zeros(cfg.S, cfg.Hkv, N, dtype=torch.int32, device=DEV)
+            lab_in[0, h] = i32_dev(tr.labels[t])
+            sizes_d = torch.zeros(cfg.S, cfg.Hkv, C, dtype=torch.int32, device=DEV)
+            offs_d = torch.zeros(cfg.S, cfg.Hkv, C + 1, dtype=torch.int32, device=DEV)
+            sidx_d = torch.zeros(cfg.S, cfg.Hkv, N, dtype=torch.int32, device=DEV)
+            ck.ck_build_metadata(sh, lab_in, 0, N, 0, C, sizes_d, offs_d, sidx_d)
+            s_o, o_o, i_o = O.build_metadata(tr.labels[t], C)
+            assert np.array_equal(sizes_d[0, h].cpu().numpy(), s_o)
+            assert np.array_equal(offs_d[0, h].cpu().numpy(), o_o)
+            assert np.array_equal(sidx_d[0, h].cpu().numpy(), i_o)
+            prev = tr.mu[t - 1] if t else keys[init[0, h].numpy()]
+            cent = torch.zeros(cfg.S, cfg.Hkv, C, 128, dtype=torch.bfloat16, device=DEV)
+            cent[0, h] = bf16_dev(prev)
+            hat = torch.zeros_like(cent)
+            f32 = torch.zeros(cfg.S, cfg.Hkv, C, 128, dtype=torch.float32, device=DEV)
+            f32[0, h] = torch.from_numpy(prev.astype(np.float32)).to(DEV)
+            ck.ck_kmeans_update(sh, w.K, sizes_d, offs_d, sidx_d, 0, C, cent, hat, f32)
+            want_mu = tr.mu[t]
+            scale = np.abs(want_mu).max()
+            assert np.abs(np64(f32[0, h]) - want_mu).max() <= 1e-5 * scale
+            # stored centroid: bf16 rounding of the mean (one ulp = 2^-8 relative)
+            nz = tr.sizes[t] > 0
+            assert np.abs(np64(cent[0, h])[nz] - want_mu[nz]).max() <= 2.0 ** -8 * scale
+            want_hat = O.unit_rows(want_mu)
+            assert np.abs(np64(hat[0, h])[nz] - want_hat[nz]).max() <= 2.0 ** -8
+            # empty clusters keep what was there
+            assert np.array_equal(np64(cent[0, h])[~nz], O.round_to_bf16(prev)[~nz])
+    print(f"near-tie rate (assignment, N={N}, C={C}): {flagged}/{total}")
+
+
+@pytest.mark.parametrize("N,C,M,n_sink", [(2048, 32, 64, 0), (4096 + 11, 50, 64, 16)])
+def test_cluster_keys_end_to_end(N, C, M, n_sink):
+    """Free-running ck_cluster_keys: structure is exact; its own centroids are the
+    means of its own clusters; agreement with the oracle's trajectory is reported."""
+    cfg = small_cfg(N, C, M)
+    w = MixtureWorkload(cfg, device=DEV)
+    n_tok = N - n_sink
+    init = sample_init_indices(w.K, C, cfg.seed, tok_begin=n_sink, tok_count=n_tok)
+    sh = ck.Shape(cfg.S, cfg.Hq, cfg.Hkv, N, C)
+    st = ck.ClusterState(sh, DEV, budget=256)
+    st.labels.fill_(-7)
+    st.cluster(w.K, init.to(DEV), n_sink, n_tok, C, cfg.n_iter)
+    torch.cuda.synchronize()
+    for h in range(cfg.Hkv):
+        keys = np64(w.K[0, h])
+        lab = st.labels[0, h].cpu().numpy()
+        assert np.all(lab[:n_sink] == -7)
+        lab = lab[n_sink:]
+        assert lab.min() >= 0 and lab.max() < C
+        sizes = st.sizes[0, h].cpu().numpy()
+        offs = st.offsets[0, h].cpu().numpy()
+        sidx = st.sorted_idx[0, h].cpu().numpy()
+        s_o, o_o, i_o = O.build_metadata(lab, C, tok_begin=n_sink)
+        assert np.array_equal(sizes, s_o) and sizes.sum() == n_tok
+        assert np.array_equal(offs, o_o)
+        assert np.array_equal(sidx[:n_tok], i_o)
+        mu_o, _ = O.update(keys[n_sink:], lab, np.zeros((C, 128)))
+        nz = sizes > 0
+        got = np64(st.centroids[0, h])
+        assert np.abs(got[nz] - mu_o[nz]).max() <= 2.0 ** -8 * np.abs(mu_o).max()
+        # against the oracle's free-running trajectory (reported, not asserted bit-exact)
+        _, lab_o, _, tr = O.kmeans(keys[n_sink:], init[0, h].numpy() - n_sink, cfg.n_iter, "bf16")
+        agree = (lab_o == lab).mean()
+        J_gpu = O.weighted_objective(keys[n_sink:], O.unit_rows(got), lab)
+        print(f"head {h}: label agreement with oracle {agree:.4f}; J gpu/oracle "
+              f"{J_gpu / tr.J[-1]:.6f}")
+        assert agree > 0.9
+        assert abs(J_gpu / tr.J[-1] - 1) < 2e-2
+
+
+def test_incremental_clustering_appends():
+    """Prefill clustering, then clustering of the generated tokens only into
+    extra clusters appended to the table (Section III-B, decode stage)."""
+    N0, C0, m, Cp = 1024, 16, 320, 4
+    cfg = small_cfg(N0, C0, 32)
+    w = MixtureWorkload(cfg, device=DEV, extra_tokens=2 * m)
+    for _ in range(2 * m):
+        w.append_token()
+    N_cap, C_cap = N0 + 2 * m, C0 + 2 * Cp
+    sh = ck.Shape(cfg.S, cfg.Hq, cfg.Hkv, N_cap, C_cap)
+    st = ck.ClusterState(sh, DEV, budget=256)
+    st.cluster(w.K, sample_init_indices(w.K, C0, 1, 0, N0).to(DEV), 0, N0, C0, 10)
+    for j in range(2):
+        init = sample_init_indices(w.K, Cp, 2 + j, N0 + j * m, m)
+        st.cluster(w.K, init.to(DEV), N0 + j * m, m, Cp, 10)
+    torch.cuda.synchronize()
+    assert st.n_clusters == C_cap
+    for h in range(cfg.Hkv):
+        lab = st.labels[0, h].cpu().numpy()
+        assert lab[:N0].max() < C0
+        for j in range(2):
+            seg = lab[N0 + j * m:N0 + (j + 1) * m]
+            assert seg.min() >= C0 + j * Cp and seg.max() < C0 + (j + 1) * Cp
+        s_o, o_o, i_o = O.build_metadata(lab, C_cap)
+        assert np.array_equal(st.sizes[0, h].cpu().numpy(), s_o)
+        assert np.array_equal(st.offsets[0, h].cpu().numpy(), o_o)
+        assert np.array_equal(st.sorted_idx[0, h].cpu().numpy(), i_o)
+        # the appended clusters are what the oracle finds on the same slice
+        keys = np64(w.K[0, h])
+        j = 1
+        init = sample_init_indices(w.K, Cp, 2 + j, N0 + j * m, m)[0, h].numpy()
+        sl = slice(N0 + j * m, N0 + (j + 1) * m)
+        mu_o, lab_o, _, tr = O.kmeans(keys[sl], init - sl.start, 10, "bf16")
+        agree = (lab[sl] - (C0 + j * Cp) == lab_o).mean()
+        print(f"head {h}: incremental label agreement with oracle {agree:.4f}")
+        assert agree > 0.95
+
+
+# ---------------------------------------------------------------- selection + gather
+def oracle_tables(w, cfg, n_iter=4):
+    """Cluster table of every head-problem computed by the oracle."""
+    out = []
+    init = sample_init_indices(w.K, cfg.C, cfg.seed)
+    for s in range(cfg.S):
+        for h in range(cfg.Hkv):
+            keys = np64(w.K[s, h, :cfg.N])
+            mu, labels, sizes, _ = O.kmeans(keys, init[s, h].numpy(), n_iter, "bf16")
+            sizes, offsets, sidx = O.build_metadata(labels, cfg.C)
+            out.append(dict(mu=O.round_to_bf16(mu), sizes=sizes, offsets=offsets, sidx=sidx,
+                            keys=keys))
+    return out
+
+
+def upload_tables(tabs, cfg, sh, budget, dtype=torch.bfloat16):
+    st = ck.ClusterState(sh, DEV, budget=budget)
+    for i, t in enumerate(tabs):
+        s, h = divmod(i, cfg.Hkv)
+        st.centroids[s, h, :cfg.C] = torch.from_numpy(t["mu"].astype(np.float32)).to(dtype).to(DEV)
+        st.sizes[s, h, :cfg.C] = i32_dev(t["sizes"])
+        st.offsets[s, h, :cfg.C + 1] = i32_dev(t["offsets"])
+        st.sorted_idx[s, h, :cfg.N] = i32_dev(t["sidx"])
+    st.n_clusters = cfg.C
+    return st
+
+
+@pytest.mark.parametrize("Hq,Hkv,S", [(2, 2, 1), (8, 2, 2), (8, 1, 1)])
+@pytest.mark.parametrize("dtype", [ck.CK_BF16, ck.CK_F32])
+def test_select_gather_attention_vs_oracle(Hq, Hkv, S, dtype):
+    cfg = small_cfg(1500, 50, 64, Hkv=Hkv, Hq=Hq, S=S, seed=3)
+    w = MixtureWorkload(cfg, device=DEV)
+    tabs = oracle_tables(w, cfg)
+    tdt = torch.bfloat16 if dtype == ck.CK_BF16 else torch.float32
+    K, V = w.K.to(tdt), w.V.to(tdt)
+    G = cfg.G
+    flagged = cases = 0
+    for budget in (1, 40, 256, 777, 1500, 4000):
+        for flags in (ck.CK_SEL_WHOLE, ck.CK_SEL_TRIM_LAST):
+            sh = ck.Shape(S, Hq, Hkv, cfg.N, cfg.C, dtype=dtype)
+            st = upload_tables(tabs, cfg, sh, budget, tdt)
+            q = w.query().to(tdt)
+            scores = torch.zeros(S, Hkv, cfg.C, dtype=torch.float32, device=DEV)
+            out = ck.decode_step(st, q, K, V, flags=flags, scores=scores)
+            torch.cuda.synchronize()
+            for i, t in enumerate(tabs):
+                s, h = divmod(i, Hkv)
+                qg = np64(q[s, h * G:(h + 1) * G])
+                Vh = np64(V[s, h])
+                r = O.decode_step(qg, t["keys"], Vh, t["mu"], t["sizes"], t["offsets"], t["sidx"],
+                                  budget, flags)
+                assert np.allclose(scores[s, h].cpu().numpy(), r["scores"], rtol=1e-5, atol=1e-4)
+                near = O.selection_near_tie(r["scores"], r["order"], r["n_sel"], NEAR_TIE)
+                cases += 1
+                flagged += int(near)
+                n_sel = int(st.n_sel_clusters[s, h])
+                n_tok = int(st.n_tokens[s, h])
+                got_idx = st.token_idx[s, h, :n_tok].cpu().numpy()
+                if not near:
+                    assert n_sel == r["n_sel"]
+                    assert int(st.n_sel_tokens[s, h]) == r["n_tok"] == n_tok
+                    assert np.array_equal(st.sel_clusters[s, h, :n_sel].cpu().numpy(),
+                                          r["order"][:n_sel])
+                    assert np.array_equal(got_idx, r["idx"])
+                # attention is judged on the GPU's own index list
+                want = O.sparse_attention(qg, t["keys"], Vh, got_idx)
+                got = np64(out[s, h * G:(h + 1) * G])
+                assert rel_err(got, want) <= ATTN_TOL[dtype], (budget, flags, s, h)
+    print(f"near-tie rate (selection): {flagged}/{cases}")
+
+
+def test_fig8_example_on_gpu():
+    """The paper's worked indexing example (Fig. 8), run through the library."""
+    N, C = 6, 3
+    sh = ck.Shape(1, 1, 1, N, C)
+    labels = i32_dev([[[2, 0, 1, 1, 1, 2]]])
+    st = ck.ClusterState(sh, DEV, budget=3, idx_stride=8)
+    ck.ck_build_metadata(sh, labels, 0, N, 0, C, st.sizes, st.offsets, st.sorted_idx)
+    assert st.sizes.flatten().tolist() == [1, 3, 2]
+    assert st.offsets.flatten().tolist() == [0, 1, 4, 6]
+    assert st.sorted_idx.flatten().tolist() == [1, 2, 3, 4, 0, 5]
+    # centroids along e0 with lengths that give the order cluster 2 > 0 > 1
+    cent = torch.zeros(1, 1, C, 128)
+    cent[0, 0, :, 0] = torch.tensor([2.0, 1.0, 3.0])
+    st.centroids.copy_(cent.to(torch.bfloat16))
+    st.n_clusters = C
+    q = torch.zeros(1, 1, 128)
+    q[0, 0, 0] = 1.0
+    q = q.to(torch.bfloat16).to(DEV)
+    for flags, budget, want_idx, want_sel in [(ck.CK_SEL_WHOLE, 3, [0, 5, 1], 2),
+                                              (ck.CK_SEL_TRIM_LAST, 3, [0, 5, 1], 2),
+                                              (ck.CK_SEL_WHOLE, 4, [0, 5, 1], 2),
+                                              (ck.CK_SEL_TRIM_LAST, 4, [0, 5, 1, 4], 3),
+                                              (ck.CK_SEL_WHOLE, 6, [0, 5, 1, 2, 3, 4], 3),
+                                              (ck.CK_SEL_WHOLE, 1, [], 0),
+                                              (ck.CK_SEL_TRIM_LAST, 1, [5], 1)]:
+        st.budget = budget
+        ck.ck_select_clusters(sh, q, st.centroids, st.sizes, C, budget, flags, st.sel_clusters,
+                              st.n_sel_clusters, st.n_sel_tokens)
+        ck.ck_gather_indices(sh, st.sel_clusters, st.n_sel_clusters, st.offsets, st.sorted_idx,
+                             budget, flags, st.token_idx, st.n_tokens)
+        assert st.sel_clusters.flatten().tolist() == [2, 0, 1]
+        assert int(st.n_sel_clusters) == want_sel
+        n = int(st.n_tokens)
+        assert n == len(want_idx) == int(st.n_sel_tokens)
+        assert st.token_idx.flatten()[:n].tolist() == want_idx
+
+
+# ---------------------------------------------------------------- attention alone
+@pytest.mark.parametrize("G", [1, 2, 4, 8])
+@pytest.mark.parametrize("dtype", [ck.CK_BF16, ck.CK_F32])
+def test_sparse_attention_ragged_sinks_recent(G, dtype):
+    S, Hkv, N = 3, 2, 5000
+    Hq = Hkv * G
+    tdt = torch.bfloat16 if dtype == ck.CK_BF16 else torch.float32
+    g = torch.Generator(device=DEV).manual_seed(G)
+    K = torch.randn(S, Hkv, N, 128, generator=g, device=DEV).to(tdt)
+    V = torch.randn(S, Hkv, N, 128, generator=g, device=DEV).to(tdt)
+    q = (2.0 * torch.randn(S, Hq, 128, generator=g, device=DEV)).to(tdt)
+    sh = ck.Shape(S, Hq, Hkv, N, 8, dtype=dtype)
+    rng = np.random.default_rng(G)
+    for max_tokens, n_sink, recent in [(1024, 0, (0, 0)), (1024, 16, (4900, 5000)),
+                                       (100, 0, (0, 0)), (64, 4, (4999, 5000)), (0, 3, (0, 0)),
+                                       (0, 0, (0, 0)), (2048, 0, (4700, 5000))]:
+        stride = max(4, (max_tokens + 3) // 4 * 4)
+        idx = np.zeros((S, Hkv, stride), dtype=np.int32)
+        n_tok = np.zeros((S, Hkv), dtype=np.int32)
+        for s in range(S):
+            for h in range(Hkv):
+                n = int(rng.integers(0, max_tokens + 1)) if max_tokens else 0
+                if (s, h) == (0, 0):
+                    n = max_tokens
+                if (s, h) == (1, 1):
+                    n = 0
+                lo, hi = n_sink, (recent[0] if recent[1] > recent[0] else N)
+                idx[s, h, :n] = rng.permutation(np.arange(lo, hi))[:n]
+                n_tok[s, h] = n
+        out = torch.full((S, Hq, 128), 7.0, dtype=tdt, device=DEV)
+        ck.ck_sparse_decode_attn(sh, q, K, V, i32_dev(idx), i32_dev(n_tok), max_tokens, out,
+                                 n_sink=n_sink, recent_begin=recent[0], recent_end=recent[1])
+        torch.cuda.synchronize()
+        for s in range(S):
+            for h in range(Hkv):
+                want = O.sparse_attention(np64(q[s, h * G:(h + 1) * G]), np64(K[s, h]),
+                                          np64(V[s, h]), idx[s, h, :n_tok[s, h]], n_sink,
+                                          recent[0], recent[1])
+                got = np64(out[s, h * G:(h + 1) * G])
+                if not want.any():
+                    assert not got.any()
+                else:
+                    assert rel_err(got, want) <= ATTN_TOL[dtype], (max_tokens, n_sink, recent, s, h)
+
+
+def test_budget_covering_all_tokens_equals_full_attention():
+    cfg = small_cfg(700, 20, 32, Hkv=2, Hq=8, seed=5)
+    w = MixtureWorkload(cfg, device=DEV)
+    tabs = oracle_tables(w, cfg)
+    sh = ck.Shape(cfg.S, cfg.Hq, cfg.Hkv, cfg.N, cfg.C)
+    st = upload_tables(tabs, cfg, sh, budget=cfg.N)
+    q = w.query()
+    out = ck.decode_step(st, q, w.K, w.V)
+    torch.cuda.synchronize()
+    for h in range(cfg.Hkv):
+        assert int(st.n_tokens[0, h]) == cfg.N
+        assert sorted(st.token_idx[0, h].cpu().tolist()) == list(range(cfg.N))
+        want = O.full_attention(np64(q[0, h * 4:(h + 1) * 4]), tabs[h]["keys"], np64(w.V[0, h]))
+        assert rel_err(np64(out[0, h * 4:(h + 1) * 4]), want) <= 2e-2
+
+
+# ---------------------------------------------------------------- full-size configuration
+def test_llama3_8b_layer_sampled():
+    """Configuration 1 at its real size, in the launch shape the benchmark times;
+    the oracle checks sampled keys of the assignment and every head-problem's
+    decode step (cheap for it: 400 centroids, 1024 recalled rows)."""
+    cfg = get_config(1)
+    w = MixtureWorkload(cfg, device=DEV)
+    init = sample_init_indices(w.K, cfg.C, cfg.seed)
+    sh = ck.Shape(cfg.S, cfg.Hq, cfg.Hkv, cfg.N, cfg.C)
+    st = ck.ClusterState(sh, DEV, budget=cfg.B)
+    st.cluster(w.K, init.to(DEV), 0, cfg.N, cfg.C, cfg.n_iter)
+    q = w.query()
+    scores = torch.zeros(cfg.S, cfg.Hkv, cfg.C, dtype=torch.float32, device=DEV)
+    out = ck.decode_step(st, q, w.K, w.V, scores=scores)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(0)
+    flagged = 0
+    for h in range(cfg.Hkv):
+        lab = st.labels[0, h].cpu().numpy()
+        sizes = st.sizes[0, h].cpu().numpy()
+        offs = st.offsets[0, h].cpu().numpy()
+        sidx = st.sorted_idx[0, h].cpu().numpy()
+        assert sizes.sum() == cfg.N and np.array_equal(np.bincount(lab, minlength=cfg.C), sizes)
+        assert np.array_equal(np.sort(sidx), np.arange(cfg.N))
+        assert np.array_equal(offs, np.concatenate([[0], np.cumsum(sizes)]))
+        assert np.all(lab[sidx] == np.repeat(np.arange(cfg.C), sizes))
+        mu = np64(st.centroids[0, h])
+        # sampled clusters: stored centroid = mean of its members
+        keys = np64(w.K[0, h])
+        for c in rng.integers(0, cfg.C, 12):
+            if sizes[c]:
+                want = keys[sidx[offs[c]:offs[c + 1]]].mean(axis=0)
+                assert np.abs(mu[c] - want).max() <= 2.0 ** -8 * np.abs(want).max() + 1e-6
+        # decode step of this head-problem
+        qg = np64(q[0, h * cfg.G:(h + 1) * cfg.G])
+        Vh = np64(w.V[0, h])
+        r = O.decode_step(qg, keys, Vh, mu, sizes, offs, sidx, cfg.B)
+        near = O.selection_near_tie(r["scores"], r["order"], r["n_sel"], NEAR_TIE)
+        flagged += int(near)
+        n_tok = int(st.n_tokens[0, h])
+        got_idx = st.token_idx[0, h, :n_tok].cpu().numpy()
+        if not near:
+            assert np.array_equal(got_idx, r["idx"])
+        assert 0 < n_tok <= cfg.B
+        want = O.sparse_attention(qg, keys, Vh, got_idx)
+        assert rel_err(np64(out[0, h * cfg.G:(h + 1) * cfg.G]), want) <= 2e-2
+    # one more assignment step from the final centroids, checked on sampled keys
+    h = 3
+    mu_hat = O.round_to_bf16(O.unit_rows(np64(st.centroids[0, h])))
+    hat = torch.zeros(cfg.S, cfg.Hkv, cfg.C, 128, dtype=torch.bfloat16, device=DEV)
+    hat[0, h] = bf16_dev(mu_hat)
+    lab2 = torch.zeros_like(st.labels)
+    ck.ck_kmeans_assign(sh, w.K, 0, cfg.N, hat, 0, cfg.C, lab2)
+    sample = rng.permutation(cfg.N)[:4096]
+    lo, _, gap = O.assign(np64(w.K[0, h])[sample], mu_hat)
+    got = lab2[0, h].cpu().numpy()[sample]
+    near = gap < NEAR_TIE
+    assert not ((got != lo) & ~near).any()
+    print(f"config 1: selection near-ties {flagged}/{cfg.Hkv}; assignment near-ties "
+          f"{int(near.sum())}/{len(sample)}")
