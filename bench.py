@@ -1,0 +1,264 @@
+#!/usr/bin/env python3
+"""Benchmark of the ClusterKV hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+A step is one pass of the whole path over one batch of synthetic input that is
+already resident in HBM: ck_cluster_keys (init, 10 x {assignment, metadata,
+update}) followed by one decode step (ck_select_clusters, ck_gather_indices,
+ck_sparse_decode_attn).  The default workload is the Llama-3-8B-shaped layer at a
+32k context with B = 1024.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_MFMA_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
+PEAK_HBM_GBPS = 8000.0             # MI355X HBM3E peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama3_8b_layer_32k")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-batch8", action="store_true",
+                    help="skip the extra decode-only measurement at batch 8, B=2048")
+    return ap.parse_args()
+
+
+def event_ms(fn, reps):
+    """Average milliseconds of fn() over reps calls, HIP events on the current stream."""
+    import torch
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        fn()
+    b.record()
+    b.synchronize()
+    return a.elapsed_time(b) / reps
+
+
+def per_launch_ms(fn, reps):
+    """Average duration of ONE call, each call bracketed by its own event pair."""
+    import torch
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in range(reps)]
+    for a, b in evs:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    ts = sorted(a.elapsed_time(b) for a, b in evs)
+    return sum(ts) / len(ts), ts[len(ts) // 2], ts[0]
+
+
+def decode_bytes(cfg, st, C):
+    """Algorithmic HBM bytes of one decode step, from the actual recalled counts."""
+    n_tok = st.n_tokens.cpu().numpy().astype("int64")
+    n_sel = st.n_sel_clusters.cpu().numpy().astype("int64")
+    hp = n_tok.size
+    d, G = cfg.d, cfg.G
+    select = hp * (C * d * 2 + C * 4 + G * d * 2) + hp * C * 4
+    gather = int(n_sel.sum()) * 4 * 2 + int(n_tok.sum()) * 4 * 2
+    attn = int(n_tok.sum()) * (d * 2 * 2 + 4) + hp * G * d * 2 * 2
+    kv = int(n_tok.sum()) * d * 2 * 2
+    return dict(select=select, gather=gather, attn=attn, total=select + gather + attn, kv=kv,
+                mean_tokens=float(n_tok.mean()))
+
+
+def cpu_baseline(cfg, w, init, q):
+    """The oracle, as it stands, on the host cores: one of the head-problems of the
+    workload, full K-means plus one decode step."""
+    import numpy as np
+    from oracle import clusterkv_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count()
+    keys = w.K[0, 0, :cfg.N].float().cpu().numpy().astype(np.float64)
+    vals = w.V[0, 0, :cfg.N].float().cpu().numpy().astype(np.float64)
+    qg = q[0, :cfg.G].float().cpu().numpy().astype(np.float64)
+    t0 = time.perf_counter()
+    mu, labels, sizes, _ = O.kmeans(keys, init[0, 0].numpy(), cfg.n_iter, "bf16")
+    sizes, offsets, sidx = O.build_metadata(labels, cfg.C)
+    t1 = time.perf_counter()
+    O.decode_step(qg, keys, vals, O.round_to_bf16(mu), sizes, offsets, sidx, cfg.B)
+    t2 = time.perf_counter()
+    return {"value": cfg.N / (t2 - t0), "unit": "keys/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"1 of {cfg.S * cfg.Hkv} head-problems of {cfg.name}: {cfg.n_iter}-iteration "
+                      f"K-means over {cfg.N} keys (C={cfg.C}) + metadata + one decode step",
+            "kmeans_s": t1 - t0, "decode_step_s": t2 - t1}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (head-problems are independent; "
+              "no multi-GPU path exists) -- rerun with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2412_03213_amd as ck
+    from ck_synth import MixtureWorkload, get_config, sample_init_indices
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    cfg = get_config(args.workload)
+    if cfg.layers != 1:
+        print("bench.py: pick a single-layer workload", file=sys.stderr)
+        sys.exit(2)
+    w = MixtureWorkload(cfg, device=dev)
+    init = sample_init_indices(w.K, cfg.C, cfg.seed)
+    init_d = init.to(dev)
+    q = w.query()
+    sh = ck.Shape(cfg.S, cfg.Hq, cfg.Hkv, cfg.N, cfg.C)
+    st = ck.ClusterState(sh, dev, budget=cfg.B)
+    HP = cfg.S * cfg.Hkv
+
+    def cluster():
+        st.n_clusters = 0
+        st.cluster(w.K, init_d, 0, cfg.N, cfg.C, cfg.n_iter)
+
+    def decode():
+        ck.decode_step(st, q, w.K, w.V)
+
+    def step():
+        cluster()
+        decode()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    keys_per_step = HP * cfg.N
+
+    # ---- parts of the step, HIP events on the launch stream ----
+    reps = max(args.steps, 10)
+    cluster_ms = event_ms(cluster, reps)
+    decode_ms = event_ms(decode, 10 * reps)
+    db = decode_bytes(cfg, st, cfg.C)
+
+    # dominant kernel: the MFMA assignment, one launch at a time
+    ws = st.cluster_ws
+    n_hat = HP * cfg.C * cfg.d
+    mu_hat = ws[:n_hat * 2].view(torch.bfloat16).view(cfg.S, cfg.Hkv, cfg.C, cfg.d)
+    labels2 = torch.empty_like(st.labels)
+
+    def assign():
+        ck.ck_kmeans_assign(sh, w.K, 0, cfg.N, mu_hat, 0, cfg.C, labels2)
+
+    for _ in range(3):
+        assign()
+    a_avg, a_med, a_min = per_launch_ms(assign, 10 * reps)
+    assign_flops = 2.0 * HP * cfg.N * cfg.C * cfg.d
+    achieved_tflops = assign_flops / (a_avg * 1e-3) / 1e12
+
+    # sparse attention alone (partial + merge kernels of one call)
+    def attn():
+        ck.ck_sparse_decode_attn(sh, q, w.K, w.V, st.token_idx, st.n_tokens, cfg.B, st.out,
+                                 workspace=st.attn_ws)
+
+    at_avg, at_med, at_min = per_launch_ms(attn, 10 * reps)
+
+    result = {
+        "metric": "decode us/layer & recalled-KV GB/s at 32k ctx, B=1024; K-means keys/s",
+        "value": keys_per_step / (ms_per_step * 1e-3),
+        "unit": "keys/s (K-means over all keys + one decode step, whole step)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "S": cfg.S, "Hq": cfg.Hq, "Hkv": cfg.Hkv, "d": cfg.d,
+                   "N": cfg.N, "C": cfg.C, "kmeans_iters": cfg.n_iter, "B": cfg.B,
+                   "mixture_centers": cfg.M, "selection": "whole clusters"},
+        "kmeans_keys_per_s": keys_per_step / (cluster_ms * 1e-3),
+        "kmeans_ms": cluster_ms,
+        "decode_us_per_layer": decode_ms * 1e3,
+        "recalled_kv_GBps": db["kv"] / (decode_ms * 1e-3) / 1e9,
+        "recalled_tokens_mean": db["mean_tokens"],
+        "roofline": {"kernel": "k_assign (bf16 MFMA assignment, one launch = one K-means "
+                               "iteration over all head-problems)",
+                     "bound": "mfma", "achieved": achieved_tflops, "peak": PEAK_BF16_MFMA_TFLOPS,
+                     "unit": "TFLOP/s", "frac": achieved_tflops / PEAK_BF16_MFMA_TFLOPS,
+                     "traffic": None, "flops_per_launch": assign_flops,
+                     "launch_ms_avg": a_avg, "launch_ms_median": a_med, "launch_ms_min": a_min},
+        "roofline_decode": {"kernels": "k_select + k_gather + k_attn_partial + k_attn_merge",
+                            "bound": "hbm", "achieved": db["total"] / (decode_ms * 1e-3) / 1e9,
+                            "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                            "frac": db["total"] / (decode_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS,
+                            "bytes_per_step": db["total"], "attn_call_us_avg": at_avg * 1e3,
+                            "attn_GBps": db["attn"] / (at_avg * 1e-3) / 1e9,
+                            "note": "batch 1: 8 head-problems, launch-latency bound"},
+    }
+
+    if not args.no_batch8:
+        result["decode_batch8_B2048"] = batch8_decode(reps)
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, w, init, q)
+    print(json.dumps(result))
+
+
+def batch8_decode(reps):
+    """Decode-only measurement on one layer of the full-depth configuration
+    (8 sequences, B = 2048), where a step moves enough bytes for the HBM roofline
+    to mean something."""
+    import torch
+    import paper_2412_03213_amd as ck
+    from ck_synth import Config, MixtureWorkload, get_config, sample_init_indices
+    c2 = get_config(2)
+    cfg = Config("full_depth_one_layer", 1, c2.S, c2.Hkv, c2.Hq, c2.d, c2.N, c2.M, c2.C,
+                 c2.n_iter, c2.B, c2.seed)
+    dev = "cuda:0"
+    w = MixtureWorkload(cfg, device=dev)
+    init = sample_init_indices(w.K, cfg.C, cfg.seed).to(dev)
+    sh = ck.Shape(cfg.S, cfg.Hq, cfg.Hkv, cfg.N, cfg.C)
+    st = ck.ClusterState(sh, dev, budget=cfg.B)
+    t_cluster = event_ms(lambda: (setattr(st, "n_clusters", 0),
+                                  st.cluster(w.K, init, 0, cfg.N, cfg.C, cfg.n_iter)), 2)
+    q = w.query()
+
+    def decode():
+        ck.decode_step(st, q, w.K, w.V)
+
+    for _ in range(5):
+        decode()
+    ms = event_ms(decode, 10 * reps)
+    db = decode_bytes(cfg, st, cfg.C)
+
+    def attn():
+        ck.ck_sparse_decode_attn(sh, q, w.K, w.V, st.token_idx, st.n_tokens, cfg.B, st.out,
+                                 workspace=st.attn_ws)
+
+    at_avg, at_med, at_min = per_launch_ms(attn, 10 * reps)
+    gbps = db["total"] / (ms * 1e-3) / 1e9
+    return {"workload": "one layer of full_depth_32layers_b8 (S=8, N=32768, C=400, B=2048)",
+            "decode_us_per_layer": ms * 1e3, "bytes_per_step": db["total"],
+            "recalled_kv_GBps": db["kv"] / (ms * 1e-3) / 1e9,
+            "recalled_tokens_mean": db["mean_tokens"],
+            "roofline": {"bound": "hbm", "achieved": gbps, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                         "frac": gbps / PEAK_HBM_GBPS},
+            "attn_call_us_avg": at_avg * 1e3, "attn_call_us_min": at_min * 1e3,
+            "attn_GBps": db["attn"] / (at_avg * 1e-3) / 1e9,
+            "kmeans_ms": t_cluster,
+            "kmeans_keys_per_s": cfg.S * cfg.Hkv * cfg.N / (t_cluster * 1e-3)}
+
+
+if __name__ == "__main__":
+    main()

@@ -125,7 +125,7 @@ int ck_kmeans_assign(const ck_shape* sh, const void* K, int64_t tok_begin, int64
   CK_OPTIONAL_PTR(best_sim);
   return hip_result(ck::launch_assign(dm, (const ck::bf16*)K, tok_begin, tok_count,
                                       (const ck::bf16*)centroids_hat, c_begin, c_count, labels,
-                                      best_sim, (hipStream_t)stream),
+                                      best_sim, nullptr, (hipStream_t)stream),
                     "assignment launch");
 }
 
@@ -147,7 +147,8 @@ int ck_build_metadata(const ck_shape* sh, const int32_t* labels, int64_t tok_beg
   if (workspace_bytes < ws.bytes)
     return fail(CK_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, ws.bytes);
   return hip_result(ck::launch_metadata(dm, labels, tok_begin, tok_count, c_begin, c_count, sizes,
-                                        offsets, sorted_idx, ws.chunk_hist, (hipStream_t)stream),
+                                        offsets, sorted_idx, ws.chunk_hist, false,
+                                        (hipStream_t)stream),
                     "metadata launch");
 }
 
@@ -203,10 +204,10 @@ int ck_cluster_keys(const ck_shape* sh, const void* K, int64_t tok_begin, int64_
   if (e != hipSuccess) return hip_result(e, "init launch");
   for (int it = 0; it < n_iter; ++it) {
     e = ck::launch_assign(dm, Kb, tok_begin, tok_count, ws.mu_hat, c_begin, c_count, labels,
-                          nullptr, st);
+                          nullptr, ws.chunk_hist, st);
     if (e != hipSuccess) return hip_result(e, "assignment launch");
     e = ck::launch_metadata(dm, labels, tok_begin, tok_count, c_begin, c_count, sizes, offsets,
-                            sorted_idx, ws.chunk_hist, st);
+                            sorted_idx, ws.chunk_hist, true, st);
     if (e != hipSuccess) return hip_result(e, "metadata launch");
     e = ck::launch_update(dm, Kb, offsets, sorted_idx, c_begin, c_count, (ck::bf16*)centroids,
                           ws.mu_hat, nullptr, st);

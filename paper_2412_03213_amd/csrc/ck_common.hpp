@@ -98,7 +98,6 @@ struct Dims {
   int dtype;
 };
 
-constexpr int SORT_CHUNK = 512;  // tokens one wavefront ranks in the counting sort
 
 struct ClusterWorkspace {
   bf16* mu_hat;       // [HP, c_count, D] unit-length centroids the assignment reads
@@ -111,13 +110,16 @@ ClusterWorkspace carve_cluster_workspace(const Dims& dm, int64_t tok_count, int 
 hipError_t launch_init_centroids(const Dims& dm, const bf16* K, const int32_t* init_idx,
                                  int c_begin, int c_count, bf16* centroids, bf16* mu_hat,
                                  hipStream_t st);
+int assign_tile_tokens(const Dims& dm, int64_t tok_count);
+// chunk_hist (nullable): [HP, n_chunks, c_count] label histogram per workgroup tile
 hipError_t launch_assign(const Dims& dm, const bf16* K, int64_t tok_begin, int64_t tok_count,
                          const bf16* mu_hat, int c_begin, int c_count, int32_t* labels,
-                         float* best_sim, hipStream_t st);
+                         float* best_sim, int32_t* chunk_hist, hipStream_t st);
+// have_hist: chunk_hist already holds the histograms (written by launch_assign)
 hipError_t launch_metadata(const Dims& dm, const int32_t* labels, int64_t tok_begin,
                            int64_t tok_count, int c_begin, int c_count, int32_t* sizes,
                            int32_t* offsets, int32_t* sorted_idx, int32_t* chunk_hist,
-                           hipStream_t st);
+                           bool have_hist, hipStream_t st);
 hipError_t launch_update(const Dims& dm, const bf16* K, const int32_t* offsets,
                          const int32_t* sorted_idx, int c_begin, int c_count, bf16* centroids,
                          bf16* mu_hat, float* centroids_f32, hipStream_t st);

@@ -20,11 +20,11 @@ constexpr int CHUNK_ROWS = 64;             // centroid rows per LDS chunk (two M
 constexpr int LDS_ROW = D + 8;             // bf16 elements per LDS row: 272 B, rows shift 4 banks
 constexpr int ASSIGN_THREADS = 256;
 
-template <int NKB>
-__global__ __launch_bounds__(ASSIGN_THREADS) void k_assign(
+template <int NKB, int WAVES_PER_SIMD>
+__global__ __launch_bounds__(ASSIGN_THREADS, WAVES_PER_SIMD) void k_assign(
     const bf16* __restrict__ K, const bf16* __restrict__ mu_hat, int32_t* __restrict__ labels,
-    float* __restrict__ best_sim, int64_t N_cap, int64_t tok_begin, int64_t tok_count,
-    int c_begin, int c_count) {
+    float* __restrict__ best_sim, int32_t* __restrict__ chunk_hist, int64_t N_cap,
+    int64_t tok_begin, int64_t tok_count, int c_begin, int c_count) {
   __shared__ __attribute__((aligned(16))) bf16 lds[2][CHUNK_ROWS * LDS_ROW];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -45,12 +45,17 @@ __global__ __launch_bounds__(ASSIGN_THREADS) void k_assign(
     for (int kk = 0; kk < 8; ++kk) bk[kb][kk] = *reinterpret_cast<const bf16x8*>(row + kk * 16);
   }
 
-  float best[NKB];
-  int bidx[NKB];
+  // Running maximum per key block as a "packed" float: the low 4 mantissa bits of
+  // every similarity are replaced by 15 - (accumulator slot), so one v_max3 chain
+  // finds value and slot together and equal values resolve to the lower centroid.
+  // The truncation moves a similarity by < 2^-19 relative, far inside the 1e-4
+  // cosine near-tie band in which labels may legitimately differ.
+  float bestp[NKB];
+  int btile[NKB];
 #pragma unroll
   for (int kb = 0; kb < NKB; ++kb) {
-    best[kb] = -INFINITY;
-    bidx[kb] = 0;
+    bestp[kb] = -INFINITY;
+    btile[kb] = 0;
   }
 
   const int n_chunks = (c_count + CHUNK_ROWS - 1) / CHUNK_ROWS;
@@ -100,19 +105,28 @@ __global__ __launch_bounds__(ASSIGN_THREADS) void k_assign(
             acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bk[kb][kk], acc[kb], 0, 0, 0);
         }
         // accumulator i of a lane is centroid row 8*(i/4) + 4*half + i%4 of the tile
-        const bool partial = row0 + 32 > c_count;      // wave-uniform
+        if (row0 + 32 > c_count) {                     // wave-uniform: zero-padded rows lose
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int c = row0 + 8 * (i >> 2) + 4 * half + (i & 3);
+          for (int i = 0; i < 16; ++i) {
+            const int c = row0 + 8 * (i >> 2) + 4 * half + (i & 3);
 #pragma unroll
-          for (int kb = 0; kb < NKB; ++kb) {
-            float v = acc[kb][i];
-            if (partial && c >= c_count) v = -INFINITY;
-            if (v > best[kb]) {                        // strict: the lower id keeps a tie
-              best[kb] = v;
-              bidx[kb] = c;
-            }
+            for (int kb = 0; kb < NKB; ++kb)
+              if (c >= c_count) acc[kb][i] = -3.0e38f;   // finite: the slot bits must not make a NaN
           }
+        }
+        const int tile_id = ch * 2 + tile;
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb) {
+          float p[16];
+#pragma unroll
+          for (int i = 0; i < 16; ++i)
+            p[i] = __uint_as_float((__float_as_uint(acc[kb][i]) & 0xFFFFFFF0u) | (uint32_t)(15 - i));
+          float m = bestp[kb];
+          m = fmaxf(fmaxf(m, p[0]), p[1]);
+#pragma unroll
+          for (int i = 2; i < 16; i += 2) m = fmaxf(fmaxf(m, p[i]), p[i + 1]);
+          btile[kb] = (m != bestp[kb]) ? tile_id : btile[kb];
+          bestp[kb] = m;
         }
       }
     }
@@ -121,40 +135,70 @@ __global__ __launch_bounds__(ASSIGN_THREADS) void k_assign(
   }
 
   // ---- lanes l and l+32 hold the two halves of each key's candidates ----
+  // (the centroid buffers are free now: the loop ended with a barrier)
+  int* hist = reinterpret_cast<int*>(&lds[0][0]);
+  if (chunk_hist) {
+    for (int c = tid; c < c_count; c += ASSIGN_THREADS) hist[c] = 0;
+    __syncthreads();
+  }
 #pragma unroll
   for (int kb = 0; kb < NKB; ++kb) {
-    const float ob = __shfl_xor(best[kb], 32, WAVE);
-    const int oi = __shfl_xor(bidx[kb], 32, WAVE);
-    if (ob > best[kb] || (ob == best[kb] && oi < bidx[kb])) {
-      best[kb] = ob;
-      bidx[kb] = oi;
+    const int slot = 15 - (int)(__float_as_uint(bestp[kb]) & 15u);
+    float best = bestp[kb];
+    int bidx = btile[kb] * 32 + 8 * (slot >> 2) + 4 * half + (slot & 3);
+    const float ob = __shfl_xor(best, 32, WAVE);
+    const int oi = __shfl_xor(bidx, 32, WAVE);
+    // compare without the slot bits so that an exact tie goes to the lower id
+    const float bt = __uint_as_float(__float_as_uint(best) & 0xFFFFFFF0u);
+    const float ot = __uint_as_float(__float_as_uint(ob) & 0xFFFFFFF0u);
+    if (ot > bt || (ot == bt && oi < bidx)) {
+      best = ob;
+      bidx = oi;
     }
     const int64_t t = wave_tok0 + kb * 32 + col;
     if (half == 0 && t < tok_count) {
       const int64_t o = (int64_t)hp * N_cap + tok_begin + t;
-      labels[o] = c_begin + bidx[kb];
-      if (best_sim) best_sim[o] = best[kb];
+      labels[o] = c_begin + bidx;
+      if (best_sim) best_sim[o] = __uint_as_float(__float_as_uint(best) & 0xFFFFFFF0u);
+      if (chunk_hist) atomicAdd(&hist[bidx], 1);       // integer counts: order does not matter
     }
   }
+  // label histogram of this workgroup's tokens = one chunk of the counting sort
+  if (chunk_hist) {
+    __syncthreads();
+    int32_t* out = chunk_hist + ((int64_t)hp * gridDim.x + blockIdx.x) * c_count;
+    for (int c = tid; c < c_count; c += ASSIGN_THREADS) out[c] = hist[c];
+  }
+}
+
+template <int NKB, int WPS>
+static void launch_assign_variant(const Dims& dm, const bf16* K, int64_t tok_begin,
+                                  int64_t tok_count, const bf16* mu_hat, int c_begin, int c_count,
+                                  int32_t* labels, float* best_sim, int32_t* chunk_hist,
+                                  hipStream_t st) {
+  dim3 grid((unsigned)((tok_count + 4 * NKB * 32 - 1) / (4 * NKB * 32)), dm.HP);
+  hipLaunchKernelGGL((k_assign<NKB, WPS>), grid, dim3(ASSIGN_THREADS), 0, st, K, mu_hat, labels,
+                     best_sim, chunk_hist, dm.N_cap, tok_begin, tok_count, c_begin, c_count);
+}
+
+// Tokens one assignment workgroup labels; also the chunk size of the counting sort
+// (the workgroup emits the label histogram of exactly its own tokens).
+// Large problems: 128 keys per wavefront (4 MFMAs per centroid fragment read).
+// Small ones (incremental clustering of a few hundred tokens): 32 keys per
+// wavefront so that more workgroups exist.
+int assign_tile_tokens(const Dims& dm, int64_t tok_count) {
+  return tok_count * dm.HP >= 64 * 1024 ? 512 : 128;
 }
 
 hipError_t launch_assign(const Dims& dm, const bf16* K, int64_t tok_begin, int64_t tok_count,
                          const bf16* mu_hat, int c_begin, int c_count, int32_t* labels,
-                         float* best_sim, hipStream_t st) {
-  // Large problems: 128 keys per wavefront (4 MFMAs per centroid fragment read).
-  // Small ones (incremental clustering of a few hundred tokens): 32 keys per
-  // wavefront so that more workgroups exist.
-  if (tok_count * dm.HP >= 64 * 1024) {
-    constexpr int NKB = 4;
-    dim3 grid((unsigned)((tok_count + 4 * NKB * 32 - 1) / (4 * NKB * 32)), dm.HP);
-    hipLaunchKernelGGL(k_assign<NKB>, grid, dim3(ASSIGN_THREADS), 0, st, K, mu_hat, labels,
-                       best_sim, dm.N_cap, tok_begin, tok_count, c_begin, c_count);
-  } else {
-    constexpr int NKB = 1;
-    dim3 grid((unsigned)((tok_count + 4 * NKB * 32 - 1) / (4 * NKB * 32)), dm.HP);
-    hipLaunchKernelGGL(k_assign<NKB>, grid, dim3(ASSIGN_THREADS), 0, st, K, mu_hat, labels,
-                       best_sim, dm.N_cap, tok_begin, tok_count, c_begin, c_count);
-  }
+                         float* best_sim, int32_t* chunk_hist, hipStream_t st) {
+  if (assign_tile_tokens(dm, tok_count) == 512)
+    launch_assign_variant<4, 2>(dm, K, tok_begin, tok_count, mu_hat, c_begin, c_count, labels,
+                                best_sim, chunk_hist, st);
+  else
+    launch_assign_variant<1, 4>(dm, K, tok_begin, tok_count, mu_hat, c_begin, c_count, labels,
+                                best_sim, chunk_hist, st);
   return hipGetLastError();
 }
 

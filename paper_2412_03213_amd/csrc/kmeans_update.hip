@@ -53,12 +53,13 @@ __device__ __forceinline__ uint64_t same_label_mask(int label, bool valid, int l
 }
 
 constexpr int SORT_THREADS = 256;                       // 4 wavefronts, one chunk each
-constexpr int SORT_ROUNDS = SORT_CHUNK / WAVE;
 
-// Pass 1: histogram of the labels of every chunk of SORT_CHUNK tokens.
+// Pass 1 (only when the assignment kernel has not already produced it): label
+// histogram of every chunk of `chunk_tokens` consecutive tokens.
 __global__ __launch_bounds__(SORT_THREADS) void k_sort_hist(
     const int32_t* __restrict__ labels, int64_t N_cap, int64_t tok_begin, int64_t tok_count,
-    int c_begin, int c_count, int label_bits, int n_chunks, int32_t* __restrict__ chunk_hist) {
+    int c_begin, int c_count, int label_bits, int n_chunks, int chunk_tokens,
+    int32_t* __restrict__ chunk_hist) {
   extern __shared__ int lds_hist[];                     // [4][c_count]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, hp = blockIdx.y;
   const int chunk = blockIdx.x * 4 + wave;
@@ -68,8 +69,8 @@ __global__ __launch_bounds__(SORT_THREADS) void k_sort_hist(
   __builtin_amdgcn_wave_barrier();
   const int32_t* lab = labels + (int64_t)hp * N_cap + tok_begin;
   const uint64_t lt = ((uint64_t)1 << lane) - 1;
-  for (int r = 0; r < SORT_ROUNDS; ++r) {
-    const int64_t t = (int64_t)chunk * SORT_CHUNK + r * WAVE + lane;
+  for (int r = 0; r < chunk_tokens / WAVE; ++r) {
+    const int64_t t = (int64_t)chunk * chunk_tokens + r * WAVE + lane;
     const bool valid = t < tok_count;
     int l = valid ? lab[t] - c_begin : 0;
     l = l < 0 ? 0 : (l >= c_count ? c_count - 1 : l);   // never index outside the table
@@ -81,62 +82,100 @@ __global__ __launch_bounds__(SORT_THREADS) void k_sort_hist(
   for (int c = lane; c < c_count; c += WAVE) out[c] = hist[c];
 }
 
-// Pass 2: per cluster, exclusive scan of the chunk counts (in place) -> sizes;
-// then the exclusive scan over clusters -> offsets.
-constexpr int SCAN_THREADS = 256;
-constexpr int SCAN_ITEMS = CK_MAX_CLUSTERS / SCAN_THREADS;  // 8 clusters per thread
+// Pass 2: per cluster, exclusive scan of the chunk counts (in place) and the
+// cluster size.  Workgroup = 64 clusters x 16 groups of chunks.
+constexpr int SCAN_THREADS = 1024;
+constexpr int SCAN_GROUPS = SCAN_THREADS / 64;
+constexpr int SCAN_REG = 16;                            // chunk counts a thread keeps in registers
 __global__ __launch_bounds__(SCAN_THREADS) void k_sort_scan(
     int32_t* __restrict__ chunk_hist, int n_chunks, int C_cap, int c_begin, int c_count,
-    int32_t* __restrict__ sizes, int32_t* __restrict__ offsets) {
-  __shared__ int tmp[SCAN_THREADS / WAVE + 1];
-  const int hp = blockIdx.x, tid = threadIdx.x;
-  int32_t* H = chunk_hist + (int64_t)hp * n_chunks * c_count;
-  int v[SCAN_ITEMS];
+    int32_t* __restrict__ sizes) {
+  __shared__ int part[SCAN_GROUPS][64];
+  const int cl = threadIdx.x & 63, grp = threadIdx.x >> 6, hp = blockIdx.y;
+  const int c = blockIdx.x * 64 + cl;
+  const int per = (n_chunks + SCAN_GROUPS - 1) / SCAN_GROUPS;
+  const int k0 = grp * per, k1 = min(k0 + per, n_chunks);
+  int32_t* H = chunk_hist + (int64_t)hp * n_chunks * c_count + c;
+  int v[SCAN_REG];
+  int sum = 0;
+  if (c < c_count) {
 #pragma unroll
-  for (int i = 0; i < SCAN_ITEMS; ++i) {
-    const int c = tid * SCAN_ITEMS + i;
-    int run = 0;
-    if (c < c_count) {
-      for (int k = 0; k < n_chunks; ++k) {
-        const int t = H[(int64_t)k * c_count + c];
-        H[(int64_t)k * c_count + c] = run;
-        run += t;
-      }
-      sizes[(int64_t)hp * C_cap + c_begin + c] = run;
-    }
-    v[i] = run;
+    for (int i = 0; i < SCAN_REG; ++i) v[i] = (k0 + i < k1) ? H[(int64_t)(k0 + i) * c_count] : 0;
+#pragma unroll
+    for (int i = 0; i < SCAN_REG; ++i) sum += v[i];
+    for (int k = k0 + SCAN_REG; k < k1; ++k) sum += H[(int64_t)k * c_count];
   }
-  block_inclusive_scan<SCAN_ITEMS>(v, tmp);
-  int32_t* off = offsets + (int64_t)hp * (C_cap + 1);
-  const int base = c_begin == 0 ? 0 : off[c_begin];
-  if (c_begin == 0 && tid == 0) off[0] = 0;
+  part[grp][cl] = sum;
+  __syncthreads();
+  int run = 0, total = 0;
 #pragma unroll
-  for (int i = 0; i < SCAN_ITEMS; ++i) {
-    const int c = tid * SCAN_ITEMS + i;
-    if (c < c_count) off[c_begin + c + 1] = base + v[i];
+  for (int g = 0; g < SCAN_GROUPS; ++g) {
+    const int t = part[g][cl];
+    if (g < grp) run += t;
+    total += t;
+  }
+  if (c < c_count) {
+#pragma unroll
+    for (int i = 0; i < SCAN_REG; ++i)
+      if (k0 + i < k1) {
+        H[(int64_t)(k0 + i) * c_count] = run;
+        run += v[i];
+      }
+    for (int k = k0 + SCAN_REG; k < k1; ++k) {
+      const int t = H[(int64_t)k * c_count];
+      H[(int64_t)k * c_count] = run;
+      run += t;
+    }
+    if (grp == 0) sizes[(int64_t)hp * C_cap + c_begin + c] = total;
   }
 }
 
-// Pass 3: stable scatter of the token rows to their sorted positions.
+// Pass 3: exclusive scan of the sizes -> offsets (every workgroup recomputes it in
+// LDS, the first one of a head-problem stores it), then the stable scatter of the
+// token rows to their sorted positions, one chunk per wavefront.
+constexpr int OFF_ITEMS = CK_MAX_CLUSTERS / SORT_THREADS;   // 8 clusters per thread
 __global__ __launch_bounds__(SORT_THREADS) void k_sort_scatter(
     const int32_t* __restrict__ labels, int64_t N_cap, int64_t tok_begin, int64_t tok_count,
-    int C_cap, int c_begin, int c_count, int label_bits, int n_chunks,
-    const int32_t* __restrict__ chunk_hist, const int32_t* __restrict__ offsets,
-    int32_t* __restrict__ sorted_idx) {
-  extern __shared__ int lds_hist[];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, hp = blockIdx.y;
+    int C_cap, int c_begin, int c_count, int label_bits, int n_chunks, int chunk_tokens,
+    const int32_t* __restrict__ chunk_hist, const int32_t* __restrict__ sizes,
+    int32_t* __restrict__ offsets, int32_t* __restrict__ sorted_idx) {
+  extern __shared__ int lds_hist[];                     // [c_count] offsets + [4][c_count]
+  __shared__ int tmp[SORT_THREADS / WAVE + 1];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hp = blockIdx.y;
+  int* offs = lds_hist;
+  int32_t* off_g = offsets + (int64_t)hp * (C_cap + 1);
+  const int base0 = c_begin == 0 ? 0 : off_g[c_begin];
+  {
+    const int32_t* sz = sizes + (int64_t)hp * C_cap + c_begin;
+    int v[OFF_ITEMS], own[OFF_ITEMS];
+#pragma unroll
+    for (int i = 0; i < OFF_ITEMS; ++i) {
+      const int c = tid * OFF_ITEMS + i;
+      own[i] = v[i] = c < c_count ? sz[c] : 0;
+    }
+    block_inclusive_scan<OFF_ITEMS>(v, tmp);
+#pragma unroll
+    for (int i = 0; i < OFF_ITEMS; ++i) {
+      const int c = tid * OFF_ITEMS + i;
+      if (c < c_count) {
+        offs[c] = base0 + v[i] - own[i];
+        if (blockIdx.x == 0) off_g[c_begin + c + 1] = base0 + v[i];
+      }
+    }
+    if (blockIdx.x == 0 && tid == 0 && c_begin == 0) off_g[0] = 0;
+  }
+  __syncthreads();
   const int chunk = blockIdx.x * 4 + wave;
-  if (chunk >= n_chunks) return;
-  volatile int* next = lds_hist + wave * c_count;       // next free position per cluster
+  if (chunk >= n_chunks) return;                        // no block barriers below
+  volatile int* next = lds_hist + (1 + wave) * c_count;  // next free position per cluster
   const int32_t* base = chunk_hist + ((int64_t)hp * n_chunks + chunk) * c_count;
-  const int32_t* off = offsets + (int64_t)hp * (C_cap + 1) + c_begin;
-  for (int c = lane; c < c_count; c += WAVE) next[c] = off[c] + base[c];
+  for (int c = lane; c < c_count; c += WAVE) next[c] = offs[c] + base[c];
   __builtin_amdgcn_wave_barrier();
   const int32_t* lab = labels + (int64_t)hp * N_cap + tok_begin;
   int32_t* out = sorted_idx + (int64_t)hp * N_cap;
   const uint64_t lt = ((uint64_t)1 << lane) - 1;
-  for (int r = 0; r < SORT_ROUNDS; ++r) {
-    const int64_t t = (int64_t)chunk * SORT_CHUNK + r * WAVE + lane;
+  for (int r = 0; r < chunk_tokens / WAVE; ++r) {
+    const int64_t t = (int64_t)chunk * chunk_tokens + r * WAVE + lane;
     const bool valid = t < tok_count;
     int l = valid ? lab[t] - c_begin : 0;
     l = l < 0 ? 0 : (l >= c_count ? c_count - 1 : l);
@@ -155,19 +194,22 @@ __global__ __launch_bounds__(SORT_THREADS) void k_sort_scatter(
 hipError_t launch_metadata(const Dims& dm, const int32_t* labels, int64_t tok_begin,
                            int64_t tok_count, int c_begin, int c_count, int32_t* sizes,
                            int32_t* offsets, int32_t* sorted_idx, int32_t* chunk_hist,
-                           hipStream_t st) {
-  const int n_chunks = (int)((tok_count + SORT_CHUNK - 1) / SORT_CHUNK);
+                           bool have_hist, hipStream_t st) {
+  const int chunk_tokens = assign_tile_tokens(dm, tok_count);
+  const int n_chunks = (int)((tok_count + chunk_tokens - 1) / chunk_tokens);
   int label_bits = 0;
   while ((1 << label_bits) < c_count) ++label_bits;
   const dim3 grid((n_chunks + 3) / 4, dm.HP);
-  const size_t lds = (size_t)4 * c_count * sizeof(int);
-  hipLaunchKernelGGL(k_sort_hist, grid, dim3(SORT_THREADS), lds, st, labels, dm.N_cap, tok_begin,
-                     tok_count, c_begin, c_count, label_bits, n_chunks, chunk_hist);
-  hipLaunchKernelGGL(k_sort_scan, dim3(dm.HP), dim3(SCAN_THREADS), 0, st, chunk_hist, n_chunks,
-                     dm.C_cap, c_begin, c_count, sizes, offsets);
-  hipLaunchKernelGGL(k_sort_scatter, grid, dim3(SORT_THREADS), lds, st, labels, dm.N_cap,
-                     tok_begin, tok_count, dm.C_cap, c_begin, c_count, label_bits, n_chunks,
-                     chunk_hist, offsets, sorted_idx);
+  if (!have_hist)
+    hipLaunchKernelGGL(k_sort_hist, grid, dim3(SORT_THREADS), (size_t)4 * c_count * sizeof(int),
+                       st, labels, dm.N_cap, tok_begin, tok_count, c_begin, c_count, label_bits,
+                       n_chunks, chunk_tokens, chunk_hist);
+  hipLaunchKernelGGL(k_sort_scan, dim3((c_count + 63) / 64, dm.HP), dim3(SCAN_THREADS), 0, st,
+                     chunk_hist, n_chunks, dm.C_cap, c_begin, c_count, sizes);
+  hipLaunchKernelGGL(k_sort_scatter, grid, dim3(SORT_THREADS),
+                     (size_t)5 * c_count * sizeof(int), st, labels, dm.N_cap, tok_begin, tok_count,
+                     dm.C_cap, c_begin, c_count, label_bits, n_chunks, chunk_tokens, chunk_hist,
+                     sizes, offsets, sorted_idx);
   return hipGetLastError();
 }
 
@@ -258,7 +300,8 @@ hipError_t launch_update(const Dims& dm, const bf16* K, const int32_t* offsets,
 ClusterWorkspace carve_cluster_workspace(const Dims& dm, int64_t tok_count, int c_count,
                                          void* base) {
   ClusterWorkspace w;
-  const int64_t n_chunks = (tok_count + SORT_CHUNK - 1) / SORT_CHUNK;
+  const int chunk_tokens = assign_tile_tokens(dm, tok_count);
+  const int64_t n_chunks = (tok_count + chunk_tokens - 1) / chunk_tokens;
   size_t mu = (size_t)dm.HP * c_count * D * sizeof(bf16);
   mu = (mu + 255) & ~(size_t)255;
   size_t hist = (size_t)dm.HP * n_chunks * c_count * sizeof(int32_t);
