@@ -174,10 +174,10 @@ int ck_kmeans_update(const ck_shape* sh, const void* K, const int32_t* sizes,
  *                     clusters if the total is smaller); the last one is cut.
  * q            [dev] [S, Hq, d].
  * n_clusters   clusters present per head-problem (<= C_cap, <= CK_MAX_CLUSTERS).
- * sel_clusters [dev] out int32 [S, Hkv, C_cap]: ALL n_clusters ids in score order;
- *              the first n_sel_clusters of them are the recalled ones.
+ * sel_clusters [dev] out int32 [S, Hkv, C_cap]: the recalled cluster ids in score
+ *              order in the first n_sel_clusters entries; the rest is unspecified.
  * n_sel_clusters, n_sel_tokens [dev] out int32 [S, Hkv].
- * scores       [dev] out fp32 [S, Hkv, C_cap], nullable.
+ * scores       [dev] out fp32 [S, Hkv, C_cap], required (the ordering step reads it).
  */
 int ck_select_clusters(const ck_shape* sh, const void* q, const void* centroids,
                        const int32_t* sizes, int32_t n_clusters, int32_t budget, uint32_t flags,
@@ -216,6 +216,27 @@ int ck_sparse_decode_attn(const ck_shape* sh, const void* q, const void* K, cons
                           int32_t max_tokens, int64_t n_sink, int64_t recent_begin,
                           int64_t recent_end, float softmax_scale, void* out, void* workspace,
                           size_t workspace_bytes, void* stream);
+
+/*
+ * One whole decode step (Sections III-C, IV-C and II-B in one call): the same
+ * results as ck_select_clusters, ck_gather_indices and ck_sparse_decode_attn in
+ * sequence (scores, sel_clusters, n_sel_clusters, n_sel_tokens, token_idx,
+ * n_tokens, out; integer outputs identical, `out` identical up to the order of
+ * fp32 additions), with fewer launches: the cluster scores are computed by one
+ * kernel, and every attention workgroup then derives the recalled prefix and its
+ * own slice of the index list itself instead of re-reading them from memory.
+ * Arguments as in the three calls; idx_stride >= budget and a multiple of 4;
+ * workspace: ck_workspace_bytes(sh, CK_WS_SPARSE_ATTN, budget + n_sink + recent
+ * window, 0).
+ */
+int ck_decode_step(const ck_shape* sh, const void* q, const void* K, const void* V,
+                   const void* centroids, const int32_t* sizes, const int32_t* offsets,
+                   const int32_t* sorted_idx, int32_t n_clusters, int32_t budget, uint32_t flags,
+                   int64_t n_sink, int64_t recent_begin, int64_t recent_end, float softmax_scale,
+                   float* scores, int32_t* sel_clusters, int32_t* n_sel_clusters,
+                   int32_t* n_sel_tokens, int32_t* token_idx, int32_t idx_stride,
+                   int32_t* n_tokens, void* out, void* workspace, size_t workspace_bytes,
+                   void* stream);
 
 #ifdef __cplusplus
 }

@@ -22,7 +22,7 @@ LIB_PATH = os.path.join(_PKG, "libclusterkv.so")
 
 EXPORTS = ("ck_version", "ck_strerror", "ck_last_error_detail", "ck_workspace_bytes",
            "ck_cluster_keys", "ck_kmeans_assign", "ck_build_metadata", "ck_kmeans_update",
-           "ck_select_clusters", "ck_gather_indices", "ck_sparse_decode_attn")
+           "ck_select_clusters", "ck_gather_indices", "ck_sparse_decode_attn", "ck_decode_step")
 
 
 class ClusterKVError(RuntimeError):
@@ -95,6 +95,9 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.ck_sparse_decode_attn.restype = ctypes.c_int
     lib.ck_sparse_decode_attn.argtypes = [SH, P, P, P, P, P, I32, I32, I64, I64, I64, F, P, P,
                                           SZ, P]
+    lib.ck_decode_step.restype = ctypes.c_int
+    lib.ck_decode_step.argtypes = [SH, P, P, P, P, P, P, P, I32, I32, U32, I64, I64, I64, F,
+                                   P, P, P, P, P, I32, P, P, P, SZ, P]
     _lib = lib
     return lib
 
@@ -183,7 +186,7 @@ def ck_kmeans_update(sh: Shape, K, sizes, offsets, sorted_idx, c_begin, c_count,
 
 
 def ck_select_clusters(sh: Shape, q, centroids, sizes, n_clusters, budget, flags, sel_clusters,
-                       n_sel_clusters, n_sel_tokens, scores=None):
+                       n_sel_clusters, n_sel_tokens, scores):
     lib = load_library()
     s = sh.c()
     _check(lib.ck_select_clusters(ctypes.byref(s), _ptr(q), _ptr(centroids), _ptr(sizes),
@@ -241,6 +244,7 @@ class ClusterState:
         self.sel_clusters = torch.zeros(S, H, C, **i32)
         self.n_sel_clusters = torch.zeros(S, H, **i32)
         self.n_sel_tokens = torch.zeros(S, H, **i32)
+        self.scores = torch.zeros(S, H, C, dtype=torch.float32, device=device)
         self.token_idx = torch.zeros(S, H, stride, **i32)
         self.n_tokens = torch.zeros(S, H, **i32)
         self.out = torch.zeros(S, sh.Hq, sh.d, dtype=sh.torch_dtype, device=device)
@@ -259,13 +263,45 @@ class ClusterState:
         self.n_clusters += c_count
 
 
+def ck_decode_step(sh: Shape, q, K, V, centroids, sizes, offsets, sorted_idx, n_clusters, budget,
+                   flags, scores, sel_clusters, n_sel_clusters, n_sel_tokens, token_idx, n_tokens,
+                   out, n_sink=0, recent_begin=0, recent_end=0, softmax_scale=None,
+                   workspace=None):
+    lib = load_library()
+    if softmax_scale is None:
+        softmax_scale = sh.d ** -0.5
+    n_recent = max(0, recent_end - recent_begin)
+    if workspace is None:
+        workspace = _workspace(
+            ck_workspace_bytes(sh, CK_WS_SPARSE_ATTN, budget + n_sink + n_recent), q)
+    stride = token_idx.shape[-1] if isinstance(token_idx, torch.Tensor) else budget
+    s = sh.c()
+    _check(lib.ck_decode_step(ctypes.byref(s), _ptr(q), _ptr(K), _ptr(V), _ptr(centroids),
+                              _ptr(sizes), _ptr(offsets), _ptr(sorted_idx), n_clusters, budget,
+                              flags, n_sink, recent_begin, recent_end, softmax_scale,
+                              _ptr(scores), _ptr(sel_clusters), _ptr(n_sel_clusters),
+                              _ptr(n_sel_tokens), _ptr(token_idx), stride, _ptr(n_tokens),
+                              _ptr(out), _ptr(workspace),
+                              workspace.numel() if isinstance(workspace, torch.Tensor) else 0,
+                              _stream(q)))
+    return workspace
+
+
 def decode_step(st: ClusterState, q, K, V, flags=CK_SEL_WHOLE, n_sink=0, recent_begin=0,
-                recent_end=0, scores=None):
-    """One decode step of the path: selection, index gather, sparse attention
-    (three library calls on the current stream).  Returns st.out."""
+                recent_end=0, fused=True):
+    """One decode step of the path on the current stream: the fused library call, or
+    (fused=False) selection, index gather and sparse attention as three calls.
+    Returns st.out."""
     sh = st.sh
+    if fused:
+        ck_decode_step(sh, q, K, V, st.centroids, st.sizes, st.offsets, st.sorted_idx,
+                       st.n_clusters, st.budget, flags, st.scores, st.sel_clusters,
+                       st.n_sel_clusters, st.n_sel_tokens, st.token_idx, st.n_tokens, st.out,
+                       n_sink=n_sink, recent_begin=recent_begin, recent_end=recent_end,
+                       workspace=st.attn_ws)
+        return st.out
     ck_select_clusters(sh, q, st.centroids, st.sizes, st.n_clusters, st.budget, flags,
-                       st.sel_clusters, st.n_sel_clusters, st.n_sel_tokens, scores)
+                       st.sel_clusters, st.n_sel_clusters, st.n_sel_tokens, st.scores)
     ck_gather_indices(sh, st.sel_clusters, st.n_sel_clusters, st.offsets, st.sorted_idx,
                       st.budget, flags, st.token_idx, st.n_tokens)
     ck_sparse_decode_attn(sh, q, K, V, st.token_idx, st.n_tokens, st.budget, st.out,

@@ -235,7 +235,7 @@ int ck_select_clusters(const ck_shape* sh, const void* q, const void* centroids,
   CK_REQUIRE_PTR(sel_clusters);
   CK_REQUIRE_PTR(n_sel_clusters);
   CK_REQUIRE_PTR(n_sel_tokens);
-  CK_OPTIONAL_PTR(scores);
+  CK_REQUIRE_PTR(scores);
   return hip_result(ck::launch_select(dm, q, centroids, sizes, n_clusters, budget, flags,
                                       sel_clusters, n_sel_clusters, n_sel_tokens, scores,
                                       (hipStream_t)stream),
@@ -305,6 +305,63 @@ int ck_sparse_decode_attn(const ck_shape* sh, const void* q, const void* K, cons
                                            max_total, n_sink, recent_begin, recent_end,
                                            softmax_scale, out, workspace, (hipStream_t)stream),
                     "attention launch");
+}
+
+int ck_decode_step(const ck_shape* sh, const void* q, const void* K, const void* V,
+                   const void* centroids, const int32_t* sizes, const int32_t* offsets,
+                   const int32_t* sorted_idx, int32_t n_clusters, int32_t budget, uint32_t flags,
+                   int64_t n_sink, int64_t recent_begin, int64_t recent_end, float softmax_scale,
+                   float* scores, int32_t* sel_clusters, int32_t* n_sel_clusters,
+                   int32_t* n_sel_tokens, int32_t* token_idx, int32_t idx_stride,
+                   int32_t* n_tokens, void* out, void* workspace, size_t workspace_bytes,
+                   void* stream) {
+  ck::Dims dm;
+  int rc = check_shape(sh, &dm, false);
+  if (rc) return rc;
+  if (n_clusters < 1 || n_clusters > sh->C_cap)
+    return fail(CK_EINVALID, "n_clusters=%d outside [1, C_cap=%d]", n_clusters, sh->C_cap);
+  if (n_clusters > CK_MAX_CLUSTERS)
+    return fail(CK_EUNSUPPORTED, "%d clusters (at most %d)", n_clusters, CK_MAX_CLUSTERS);
+  if (budget < 1) return fail(CK_EINVALID, "budget=%d must be positive", budget);
+  if (flags > CK_SEL_TRIM_LAST) return fail(CK_EINVALID, "unknown flags 0x%x", flags);
+  if (idx_stride < budget)
+    return fail(CK_EINVALID, "idx_stride=%d smaller than budget=%d", idx_stride, budget);
+  if (idx_stride % 4 != 0)
+    return fail(CK_EMISALIGNED, "idx_stride=%d not a multiple of 4", idx_stride);
+  if (n_sink < 0 || n_sink > sh->N_cap)
+    return fail(CK_EINVALID, "n_sink=%lld outside [0, N_cap]", (long long)n_sink);
+  if (recent_end < recent_begin) recent_end = recent_begin;
+  if (recent_begin < 0 || recent_end > sh->N_cap)
+    return fail(CK_EINVALID, "recent window [%lld, %lld) outside [0, N_cap]",
+                (long long)recent_begin, (long long)recent_end);
+  if (!(softmax_scale > 0.f)) return fail(CK_EINVALID, "softmax_scale must be positive");
+  CK_REQUIRE_PTR(q);
+  CK_REQUIRE_PTR(K);
+  CK_REQUIRE_PTR(V);
+  CK_REQUIRE_PTR(centroids);
+  CK_REQUIRE_PTR(sizes);
+  CK_REQUIRE_PTR(offsets);
+  CK_REQUIRE_PTR(sorted_idx);
+  CK_REQUIRE_PTR(scores);
+  CK_REQUIRE_PTR(sel_clusters);
+  CK_REQUIRE_PTR(n_sel_clusters);
+  CK_REQUIRE_PTR(n_sel_tokens);
+  CK_REQUIRE_PTR(token_idx);
+  CK_REQUIRE_PTR(n_tokens);
+  CK_REQUIRE_PTR(out);
+  const int64_t max_total = (int64_t)budget + n_sink + (recent_end - recent_begin);
+  if (max_total > (int64_t)1 << 30) return fail(CK_EUNSUPPORTED, "attended set too large");
+  const size_t need = ck::attn_workspace_bytes(dm, max_total);
+  if (!workspace) return fail(CK_EWORKSPACE, "workspace is NULL");
+  if (!aligned16(workspace)) return fail(CK_EMISALIGNED, "workspace is not 16-byte aligned");
+  if (workspace_bytes < need)
+    return fail(CK_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+  return hip_result(
+      ck::launch_decode_fused(dm, q, K, V, centroids, sizes, offsets, sorted_idx, n_clusters,
+                              budget, flags, n_sink, recent_begin, recent_end, softmax_scale,
+                              scores, sel_clusters, n_sel_clusters, n_sel_tokens, token_idx,
+                              idx_stride, n_tokens, out, workspace, (hipStream_t)stream),
+      "fused decode launch");
 }
 
 }  // extern "C"

@@ -127,6 +127,16 @@ hipError_t launch_select(const Dims& dm, const void* q, const void* centroids,
                          const int32_t* sizes, int n_clusters, int budget, uint32_t flags,
                          int32_t* sel_clusters, int32_t* n_sel_clusters, int32_t* n_sel_tokens,
                          float* scores, hipStream_t st);
+hipError_t launch_score(const Dims& dm, const void* q, const void* centroids, int n_clusters,
+                        float* scores, hipStream_t st);
+hipError_t launch_decode_fused(const Dims& dm, const void* q, const void* K, const void* V,
+                               const void* centroids, const int32_t* sizes,
+                               const int32_t* offsets, const int32_t* sorted_idx, int n_clusters,
+                               int budget, uint32_t flags, int64_t n_sink, int64_t recent_begin,
+                               int64_t recent_end, float softmax_scale, float* scores,
+                               int32_t* sel_clusters, int32_t* n_sel_clusters,
+                               int32_t* n_sel_tokens, int32_t* token_idx, int idx_stride,
+                               int32_t* n_tokens, void* out, void* workspace, hipStream_t st);
 hipError_t launch_gather(const Dims& dm, const int32_t* sel_clusters,
                          const int32_t* n_sel_clusters, const int32_t* offsets,
                          const int32_t* sorted_idx, int budget, uint32_t flags,

@@ -1,70 +1,172 @@
 // Sparse GQA decode attention over the recalled tokens (paper Section II-B:
-// softmax(q K_S^T / sqrt(d)) V_S with K_S, V_S the selected rows).
+// softmax(q K_S^T / sqrt(d)) V_S with K_S, V_S the selected rows), alone or fused
+// with the cluster selection and index generation of Sections III-C / IV-C.
 //
 // HBM-bound: every recalled K and V row (256 B in bf16) is read exactly once per
 // KV head and shared by the G query heads of the group.  A 16-lane group owns one
 // token at a time (16 B of the row per lane, so a wavefront load instruction
-// covers four whole rows = eight 128-byte lines); the token list of a
-// head-problem is split over several workgroups (split-KV) so that a batch of a
+// covers four whole rows = eight 128-byte lines); the attended positions of a
+// head-problem are split over several workgroups (split-KV) so that a batch of a
 // few sequences still fills 256 CUs, and a small second kernel merges the
-// partial (max, sum, accumulator) triples.
-#include "ck_common.hpp"
+// partial (max, sum, accumulator) triples.  Inside a workgroup the token rows of
+// its positions are resolved into LDS first, so the K/V loads of the next step
+// are always in flight while the current one is reduced.
+//
+// Fused mode: every workgroup of a head-problem repeats the (cheap, LDS-only)
+// selection of the recalled cluster prefix from the precomputed scores and maps
+// its own positions through the cluster-contiguous index directly; the index
+// list is still written out (each workgroup its own part) but never re-read.
+#include <type_traits>
+
+#include "decode_common.hpp"
 
 namespace ck {
 
-constexpr int ATT_THREADS = 256;           // 4 wavefronts = 16 token slots per workgroup step
-constexpr int ATT_UNROLL = 4;              // steps in flight per wavefront
+constexpr int ATT_THREADS = SELP_THREADS;  // 4 wavefronts = 16 token slots per workgroup step
+constexpr int ATT_UNROLL = 4;              // token slots in flight per 16-lane group
 constexpr int ATT_STEP_TOKENS = 16 * ATT_UNROLL;   // 64 tokens per workgroup iteration
+constexpr int ATT_MAX_CHUNK = 4096;        // positions one workgroup may own (rows held in LDS)
 constexpr float NEG_BIG = -1.0e30f;        // "no token yet": finite so that differences stay finite
+constexpr int ATT_TARGET_WGS = 512;        // 2 per CU on 256 CUs
 constexpr int PART_STRIDE = D + 2;         // floats per (split, query head): max, sum, acc[128]
 
-template <typename T>
-__device__ __forceinline__ void load_row8(const T* p, float (&v)[8]);
-template <>
-__device__ __forceinline__ void load_row8<bf16>(const bf16* p, float (&v)[8]) {
-  const uint4 w = *reinterpret_cast<const uint4*>(p);
-  v[0] = lo_bf16(w.x); v[1] = hi_bf16(w.x); v[2] = lo_bf16(w.y); v[3] = hi_bf16(w.y);
-  v[4] = lo_bf16(w.z); v[5] = hi_bf16(w.z); v[6] = lo_bf16(w.w); v[7] = hi_bf16(w.w);
-}
-template <>
-__device__ __forceinline__ void load_row8<float>(const float* p, float (&v)[8]) {
-  const float4 a = reinterpret_cast<const float4*>(p)[0], b = reinterpret_cast<const float4*>(p)[1];
-  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-}
+template <typename T> struct RawRow;
+template <> struct RawRow<bf16> {
+  uint4 w;
+  __device__ __forceinline__ void load(const bf16* p) { w = *reinterpret_cast<const uint4*>(p); }
+  __device__ __forceinline__ void unpack(float (&v)[8]) const {
+    v[0] = lo_bf16(w.x); v[1] = hi_bf16(w.x); v[2] = lo_bf16(w.y); v[3] = hi_bf16(w.y);
+    v[4] = lo_bf16(w.z); v[5] = hi_bf16(w.z); v[6] = lo_bf16(w.w); v[7] = hi_bf16(w.w);
+  }
+};
+template <> struct RawRow<float> {
+  float4 a, b;
+  __device__ __forceinline__ void load(const float* p) {
+    a = reinterpret_cast<const float4*>(p)[0];
+    b = reinterpret_cast<const float4*>(p)[1];
+  }
+  __device__ __forceinline__ void unpack(float (&v)[8]) const {
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  }
+};
+
 __device__ __forceinline__ void store_out(bf16* p, float v) {
   *reinterpret_cast<uint16_t*>(p) = float_to_bf16_bits(v);
 }
 __device__ __forceinline__ void store_out(float* p, float v) { *p = v; }
 
+struct AttnArgs {
+  const void *q, *K, *V;
+  void* out;
+  float* part;
+  // given index list
+  const int32_t* token_idx;
+  const int32_t* n_tokens;
+  // fused selection
+  const float* scores;
+  const int32_t *sizes, *offsets, *sorted_idx;
+  int32_t *sel_clusters, *n_sel_clusters, *n_sel_tokens, *token_idx_out, *n_tokens_out;
+  int n_clusters, budget, trim, C_cap;
+  // common
+  int idx_stride, max_tokens, Hq, Hkv, n_sink, n_recent, chunk, n_split;
+  int64_t N_cap, recent_begin;
+  float scale_log2e;
+};
+
+template <int G>
+struct AttnPlainLds {
+  int rows[ATT_MAX_CHUNK];
+  float red[4 * G * PART_STRIDE];
+};
+
 // Attended position p of a head-problem -> token row:
 //   [0, n_sink) sinks, then the recalled list, then [recent_begin, recent_end).
-template <typename T, int G>
-__global__ __launch_bounds__(ATT_THREADS) void k_attn_partial(
-    const T* __restrict__ q, const T* __restrict__ K, const T* __restrict__ V,
-    const int32_t* __restrict__ token_idx, const int32_t* __restrict__ n_tokens, int idx_stride,
-    int max_tokens, int Hq, int Hkv, int64_t N_cap, int n_sink, int64_t recent_begin,
-    int n_recent, float scale_log2e, int chunk, int n_split, float* __restrict__ part,
-    T* __restrict__ out) {
-  __shared__ float red[4][G][PART_STRIDE];
+template <typename T, int G, bool FUSED>
+__global__ __launch_bounds__(ATT_THREADS) void k_attn_partial(const AttnArgs a) {
+  using Lds = typename std::conditional<FUSED, SelectLds, AttnPlainLds<G>>::type;
+  __shared__ Lds lds;
+  int* rows;
+  float* red;
   const int split = blockIdx.x, hp = blockIdx.y, tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6, l16 = tid & 15, slot = tid >> 4;  // 16 slots
-  const int s = hp / Hkv, h = hp % Hkv;
-
-  int n_idx = n_tokens ? n_tokens[hp] : 0;
-  n_idx = n_idx < 0 ? 0 : (n_idx > max_tokens ? max_tokens : n_idx);
-  const int n_total = n_sink + n_idx + n_recent;
-  const int p_begin = split * chunk;
-  int p_end = p_begin + chunk;
-  if (p_end > n_total) p_end = n_total;
+  const int s = hp / a.Hkv, h = hp % a.Hkv;
+  const T* q = static_cast<const T*>(a.q);
 
   // this lane's 8 channels of every query head of the group, pre-scaled
   float qv[G][8];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
-    load_row8<T>(q + ((int64_t)s * Hq + h * G + g) * D + l16 * 8, qv[g]);
+    load_row8<T>(q + ((int64_t)s * a.Hq + h * G + g) * D + l16 * 8, qv[g]);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) qv[g][j] *= scale_log2e;
+    for (int j = 0; j < 8; ++j) qv[g][j] *= a.scale_log2e;
   }
+
+  int n_idx;
+  if constexpr (FUSED) {
+    SelectLds& L = lds;
+    select_prefix(L, a.scores + (int64_t)hp * a.C_cap, a.sizes + (int64_t)hp * a.C_cap,
+                  a.offsets + (int64_t)hp * (a.C_cap + 1), a.n_clusters, a.budget, a.trim);
+    n_idx = L.n_tok;
+    if (split == 0) {
+      for (int j = tid; j < L.n_sel; j += ATT_THREADS)
+        a.sel_clusters[(int64_t)hp * a.C_cap + j] = L.ord[j];
+      if (tid == 0) {
+        a.n_sel_clusters[hp] = L.n_sel;
+        a.n_sel_tokens[hp] = n_idx;
+        a.n_tokens_out[hp] = n_idx;
+      }
+    }
+    rows = reinterpret_cast<int*>(L.key);               // key + ssz: free after the ranking
+    red = reinterpret_cast<float*>(L.ord);              // ord..cand: free after the rows are known
+  } else {
+    rows = lds.rows;
+    red = lds.red;
+    n_idx = a.n_tokens ? a.n_tokens[hp] : 0;
+    n_idx = n_idx < 0 ? 0 : (n_idx > a.max_tokens ? a.max_tokens : n_idx);
+  }
+  const int n_total = a.n_sink + n_idx + a.n_recent;
+  const int p_begin = split * a.chunk;
+  int p_end = p_begin + a.chunk;
+  if (p_end > n_total) p_end = n_total;
+  const int n_pos = p_end > p_begin ? p_end - p_begin : 0;
+
+  // ---- token row of every position this workgroup owns ----
+  for (int i = tid; i < n_pos; i += ATT_THREADS) {
+    const int p = p_begin + i;
+    int64_t row;
+    if (p < a.n_sink) {
+      row = p;
+    } else if (p < a.n_sink + n_idx) {
+      const int qpos = p - a.n_sink;
+      if constexpr (FUSED) {
+        SelectLds& L = lds;
+        // smallest j with cum[j] > qpos (empty clusters in the prefix are skipped)
+        int lo = 0, hi = L.n_sel - 1;
+        while (lo < hi) {
+          const int mid = (lo + hi) >> 1;
+          if (L.cum[mid] > qpos) hi = mid; else lo = mid + 1;
+        }
+        const int c = L.ord[lo];
+        const int prev = lo ? L.cum[lo - 1] : 0;
+        const int size = L.cum[lo] - prev;
+        int take = a.budget - prev;                     // a cut cluster keeps its trailing entries
+        take = take > size ? size : take;
+        const int beg = L.full_rank ? a.offsets[(int64_t)hp * (a.C_cap + 1) + c] : L.cbeg[lo];
+        int64_t src = (int64_t)beg + (size - take) + (qpos - prev);
+        src = src < 0 ? 0 : (src >= a.N_cap ? a.N_cap - 1 : src);
+        row = a.sorted_idx[(int64_t)hp * a.N_cap + src];
+        a.token_idx_out[(int64_t)hp * a.idx_stride + qpos] = (int32_t)row;
+      } else {
+        row = a.token_idx[(int64_t)hp * a.idx_stride + qpos];
+      }
+    } else {
+      row = a.recent_begin + (p - a.n_sink - n_idx);
+    }
+    row = row < 0 ? 0 : (row >= a.N_cap ? a.N_cap - 1 : row);
+    rows[i] = (int)row;
+  }
+  __syncthreads();
+
   float m[G], l[G], acc[G][8];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
@@ -74,40 +176,41 @@ __global__ __launch_bounds__(ATT_THREADS) void k_attn_partial(
     for (int j = 0; j < 8; ++j) acc[g][j] = 0.f;
   }
 
-  const T* Khp = K + (int64_t)hp * N_cap * D + l16 * 8;
-  const T* Vhp = V + (int64_t)hp * N_cap * D + l16 * 8;
-  const int32_t* idx = token_idx ? token_idx + (int64_t)hp * idx_stride : nullptr;
-
-  for (int p0 = p_begin; p0 < p_end; p0 += ATT_STEP_TOKENS) {
-    float kv[ATT_UNROLL][8], vv[ATT_UNROLL][8];
-    bool ok[ATT_UNROLL];
+  const T* Khp = static_cast<const T*>(a.K) + (int64_t)hp * a.N_cap * D + l16 * 8;
+  const T* Vhp = static_cast<const T*>(a.V) + (int64_t)hp * a.N_cap * D + l16 * 8;
+  RawRow<T> kc[ATT_UNROLL], vc[ATT_UNROLL], kn[ATT_UNROLL], vn[ATT_UNROLL];
+  auto fetch = [&](int i0, RawRow<T>(&kr)[ATT_UNROLL], RawRow<T>(&vr)[ATT_UNROLL]) {
 #pragma unroll
     for (int u = 0; u < ATT_UNROLL; ++u) {
-      const int p = p0 + u * 16 + slot;
-      ok[u] = p < p_end;
-      int64_t row = 0;
-      if (ok[u]) {
-        if (p < n_sink) row = p;
-        else if (p < n_sink + n_idx) row = idx[p - n_sink];
-        else row = recent_begin + (p - n_sink - n_idx);
-        row = row < 0 ? 0 : (row >= N_cap ? N_cap - 1 : row);
-      }
-      load_row8<T>(Khp + row * D, kv[u]);
-      load_row8<T>(Vhp + row * D, vv[u]);
+      const int i = i0 + u * 16 + slot;
+      const int64_t row = i < n_pos ? rows[i] : 0;
+      kr[u].load(Khp + row * D);
+      vr[u].load(Vhp + row * D);
     }
+  };
+  if (n_pos > 0) fetch(0, kc, vc);
+  for (int i0 = 0; i0 < n_pos; i0 += ATT_STEP_TOKENS) {
+    if (i0 + ATT_STEP_TOKENS < n_pos) fetch(i0 + ATT_STEP_TOKENS, kn, vn);
+    float kv[ATT_UNROLL][8];
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-      float sc[ATT_UNROLL];
-      float mx = m[g];
+    for (int u = 0; u < ATT_UNROLL; ++u) kc[u].unpack(kv[u]);
+    float sc[G][ATT_UNROLL];
+#pragma unroll
+    for (int g = 0; g < G; ++g)
 #pragma unroll
       for (int u = 0; u < ATT_UNROLL; ++u) {
         float d = 0.f;
 #pragma unroll
         for (int j = 0; j < 8; ++j) d = fmaf(qv[g][j], kv[u][j], d);
         d = row16_sum(d);
-        sc[u] = ok[u] ? d : -INFINITY;
-        mx = fmaxf(mx, sc[u]);
+        sc[g][u] = (i0 + u * 16 + slot < n_pos) ? d : -INFINITY;
       }
+    float pw[G][ATT_UNROLL];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      float mx = m[g];
+#pragma unroll
+      for (int u = 0; u < ATT_UNROLL; ++u) mx = fmaxf(mx, sc[g][u]);
       const float corr = __builtin_amdgcn_exp2f(m[g] - mx);
       m[g] = mx;
       float ls = l[g] * corr;
@@ -115,16 +218,29 @@ __global__ __launch_bounds__(ATT_THREADS) void k_attn_partial(
       for (int j = 0; j < 8; ++j) acc[g][j] *= corr;
 #pragma unroll
       for (int u = 0; u < ATT_UNROLL; ++u) {
-        const float pw = __builtin_amdgcn_exp2f(sc[u] - mx);
-        ls += pw;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) acc[g][j] = fmaf(pw, vv[u][j], acc[g][j]);
+        pw[g][u] = __builtin_amdgcn_exp2f(sc[g][u] - mx);
+        ls += pw[g][u];
       }
       l[g] = ls;
+    }
+#pragma unroll
+    for (int u = 0; u < ATT_UNROLL; ++u) {
+      float vv[8];
+      vc[u].unpack(vv);
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[g][j] = fmaf(pw[g][u], vv[j], acc[g][j]);
+    }
+#pragma unroll
+    for (int u = 0; u < ATT_UNROLL; ++u) {
+      kc[u] = kn[u];
+      vc[u] = vn[u];
     }
   }
 
   // ---- combine the 4 slots of a wavefront (lanes l16 + 16*k) ----
+  if constexpr (FUSED) __syncthreads();   // red aliases arrays the row resolution read
 #pragma unroll
   for (int g = 0; g < G; ++g) {
     float mx = fmaxf(m[g], __shfl_xor(m[g], 16, WAVE));
@@ -135,38 +251,41 @@ __global__ __launch_bounds__(ATT_THREADS) void k_attn_partial(
     ls += __shfl_xor(ls, 32, WAVE);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      float a = acc[g][j] * w;
-      a += __shfl_xor(a, 16, WAVE);
-      a += __shfl_xor(a, 32, WAVE);
-      acc[g][j] = a;
+      float v = acc[g][j] * w;
+      v += __shfl_xor(v, 16, WAVE);
+      v += __shfl_xor(v, 32, WAVE);
+      acc[g][j] = v;
     }
     if (lane < 16) {
-      red[wave][g][0] = mx;
-      red[wave][g][1] = ls;
+      float* r = red + (wave * G + g) * PART_STRIDE;
+      r[0] = mx;
+      r[1] = ls;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) red[wave][g][2 + l16 * 8 + j] = acc[g][j];
+      for (int j = 0; j < 8; ++j) r[2 + l16 * 8 + j] = acc[g][j];
     }
   }
   __syncthreads();
   // ---- combine the 4 wavefronts: thread = (query head g, channel pair) ----
+  T* out = static_cast<T*>(a.out);
   for (int e = tid; e < G * (D / 2); e += ATT_THREADS) {
     const int g = e / (D / 2), c2 = (e % (D / 2)) * 2;
-    float mx = fmaxf(fmaxf(red[0][g][0], red[1][g][0]), fmaxf(red[2][g][0], red[3][g][0]));
-    float ls = 0.f, a0 = 0.f, a1 = 0.f;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const float f = __builtin_amdgcn_exp2f(red[w][g][0] - mx);
-      ls += red[w][g][1] * f;
-      a0 += red[w][g][2 + c2] * f;
-      a1 += red[w][g][3 + c2] * f;
-    }
-    if (n_split == 1) {
+    const float* r0 = red + (0 * G + g) * PART_STRIDE;
+    const float* r1 = red + (1 * G + g) * PART_STRIDE;
+    const float* r2 = red + (2 * G + g) * PART_STRIDE;
+    const float* r3 = red + (3 * G + g) * PART_STRIDE;
+    const float mx = fmaxf(fmaxf(r0[0], r1[0]), fmaxf(r2[0], r3[0]));
+    const float f0 = __builtin_amdgcn_exp2f(r0[0] - mx), f1 = __builtin_amdgcn_exp2f(r1[0] - mx);
+    const float f2 = __builtin_amdgcn_exp2f(r2[0] - mx), f3 = __builtin_amdgcn_exp2f(r3[0] - mx);
+    const float ls = ((r0[1] * f0 + r1[1] * f1) + r2[1] * f2) + r3[1] * f3;
+    const float a0 = ((r0[2 + c2] * f0 + r1[2 + c2] * f1) + r2[2 + c2] * f2) + r3[2 + c2] * f3;
+    const float a1 = ((r0[3 + c2] * f0 + r1[3 + c2] * f1) + r2[3 + c2] * f2) + r3[3 + c2] * f3;
+    if (a.n_split == 1) {
       const float inv = ls > 0.f ? 1.0f / ls : 0.f;
-      T* o = out + ((int64_t)s * Hq + h * G + g) * D + c2;
+      T* o = out + ((int64_t)s * a.Hq + h * G + g) * D + c2;
       store_out(o, a0 * inv);
       store_out(o + 1, a1 * inv);
     } else {
-      float* pr = part + (((int64_t)hp * n_split + split) * G + g) * PART_STRIDE;
+      float* pr = a.part + (((int64_t)hp * a.n_split + split) * G + g) * PART_STRIDE;
       if (c2 == 0) {
         pr[0] = mx;
         pr[1] = ls;
@@ -177,7 +296,9 @@ __global__ __launch_bounds__(ATT_THREADS) void k_attn_partial(
   }
 }
 
-// out[hq] = sum_i acc_i 2^(m_i - M) / sum_i l_i 2^(m_i - M)
+// out[hq] = sum_i acc_i 2^(m_i - M) / sum_i l_i 2^(m_i - M); the partials of up to
+// MERGE_BATCH splits are loaded together so that their latencies overlap.
+constexpr int MERGE_BATCH = 16;
 template <typename T>
 __global__ __launch_bounds__(D) void k_attn_merge(const float* __restrict__ part, int n_split,
                                                   int G, int Hq, int Hkv, T* __restrict__ out) {
@@ -186,24 +307,45 @@ __global__ __launch_bounds__(D) void k_attn_merge(const float* __restrict__ part
   const int hp = s * Hkv + hq / G, g = hq % G, t = threadIdx.x;
   const float* base = part + (((int64_t)hp * n_split) * G + g) * PART_STRIDE;
   const int64_t stride = (int64_t)G * PART_STRIDE;
-  float mx = NEG_BIG;
-  for (int i = 0; i < n_split; ++i) mx = fmaxf(mx, base[i * stride]);
-  float ls = 0.f, a = 0.f;
-  for (int i = 0; i < n_split; ++i) {
-    const float f = __builtin_amdgcn_exp2f(base[i * stride] - mx);
-    ls += base[i * stride + 1] * f;
-    a += base[i * stride + 2 + t] * f;
+  float M = NEG_BIG, ls = 0.f, acc = 0.f;
+  for (int i0 = 0; i0 < n_split; i0 += MERGE_BATCH) {
+    float mi[MERGE_BATCH], li[MERGE_BATCH], ai[MERGE_BATCH];
+#pragma unroll
+    for (int i = 0; i < MERGE_BATCH; ++i) {
+      const bool ok = i0 + i < n_split;
+      const float* p = base + (int64_t)(ok ? i0 + i : 0) * stride;
+      mi[i] = ok ? p[0] : NEG_BIG;
+      li[i] = ok ? p[1] : 0.f;
+      ai[i] = ok ? p[2 + t] : 0.f;
+    }
+    float mx = M;
+#pragma unroll
+    for (int i = 0; i < MERGE_BATCH; ++i) mx = fmaxf(mx, mi[i]);
+    const float corr = __builtin_amdgcn_exp2f(M - mx);
+    ls *= corr;
+    acc *= corr;
+    M = mx;
+#pragma unroll
+    for (int i = 0; i < MERGE_BATCH; ++i) {
+      const float f = __builtin_amdgcn_exp2f(mi[i] - mx);
+      ls += li[i] * f;
+      acc += ai[i] * f;
+    }
   }
-  store_out(out + (int64_t)hq_lin * D + t, ls > 0.f ? a / ls : 0.f);
+  store_out(out + (int64_t)hq_lin * D + t, ls > 0.f ? acc / ls : 0.f);
 }
 
 int attn_num_splits(const Dims& dm, int64_t max_total) {
-  // aim for ~4 workgroups per CU, but keep at least one full step of tokens per workgroup
-  int64_t by_work = (max_total + ATT_STEP_TOKENS - 1) / ATT_STEP_TOKENS;
-  int64_t by_fill = (1024 + dm.HP - 1) / dm.HP;
+  // aim for two workgroups per CU (measured best: longer token runs per workgroup keep
+  // the prefetch pipeline full and the merge small), but keep at least one full step
+  // of tokens per workgroup and never more positions than its LDS row table holds
+  const int64_t by_work = (max_total + ATT_STEP_TOKENS - 1) / ATT_STEP_TOKENS;
+  const int64_t by_fill = (ATT_TARGET_WGS + dm.HP - 1) / dm.HP;
   int64_t n = by_work < by_fill ? by_work : by_fill;
-  if (n < 1) n = 1;
   if (n > 64) n = 64;
+  const int64_t need = (max_total + ATT_MAX_CHUNK - 1) / ATT_MAX_CHUNK;
+  if (n < need) n = need;
+  if (n < 1) n = 1;
   return (int)n;
 }
 
@@ -213,47 +355,49 @@ size_t attn_workspace_bytes(const Dims& dm, int64_t max_total) {
   return (b + 255) & ~(size_t)255;
 }
 
-template <typename T, int G>
-static void launch_partial(const Dims& dm, const void* q, const void* K, const void* V,
-                           const int32_t* token_idx, const int32_t* n_tokens, int idx_stride,
-                           int max_tokens, int n_sink, int64_t recent_begin, int n_recent,
-                           float scale_log2e, int chunk, int n_split, float* part, void* out,
-                           hipStream_t st) {
-  hipLaunchKernelGGL((k_attn_partial<T, G>), dim3(n_split, dm.HP), dim3(ATT_THREADS), 0, st,
-                     (const T*)q, (const T*)K, (const T*)V, token_idx, n_tokens, idx_stride,
-                     max_tokens, dm.Hq, dm.Hkv, dm.N_cap, n_sink, recent_begin, n_recent,
-                     scale_log2e, chunk, n_split, part, (T*)out);
-}
-
-template <typename T>
-static hipError_t launch_attn_t(const Dims& dm, const void* q, const void* K, const void* V,
-                                const int32_t* token_idx, const int32_t* n_tokens, int idx_stride,
-                                int64_t max_total, int64_t n_sink, int64_t recent_begin,
-                                int64_t recent_end, float softmax_scale, void* out,
-                                void* workspace, hipStream_t st) {
-  const int n_recent = (int)(recent_end > recent_begin ? recent_end - recent_begin : 0);
-  const int max_tokens = (int)(max_total - n_sink - n_recent);
+template <typename T, bool FUSED>
+static hipError_t launch_attn_t(const Dims& dm, AttnArgs a, int64_t max_total, hipStream_t st) {
   const int n_split = attn_num_splits(dm, max_total);
   int chunk = (int)((max_total + n_split - 1) / n_split);
-  chunk = (chunk + 15) & ~15;
-  if (chunk < 16) chunk = 16;
-  const float scale_log2e = softmax_scale * 1.4426950408889634f;
-  float* part = reinterpret_cast<float*>(workspace);
-#define CK_ATT(GG)                                                                              \
-  launch_partial<T, GG>(dm, q, K, V, token_idx, n_tokens, idx_stride, max_tokens, (int)n_sink, \
-                        recent_begin, n_recent, scale_log2e, chunk, n_split, part, out, st)
+  chunk = (chunk + ATT_STEP_TOKENS - 1) / ATT_STEP_TOKENS * ATT_STEP_TOKENS;
+  if (chunk < ATT_STEP_TOKENS) chunk = ATT_STEP_TOKENS;
+  if (chunk > ATT_MAX_CHUNK) return hipErrorInvalidValue;
+  a.chunk = chunk;
+  a.n_split = n_split;
+  const dim3 grid(n_split, dm.HP), block(ATT_THREADS);
   switch (dm.G) {
-    case 1: CK_ATT(1); break;
-    case 2: CK_ATT(2); break;
-    case 4: CK_ATT(4); break;
-    case 8: CK_ATT(8); break;
+    case 1: hipLaunchKernelGGL((k_attn_partial<T, 1, FUSED>), grid, block, 0, st, a); break;
+    case 2: hipLaunchKernelGGL((k_attn_partial<T, 2, FUSED>), grid, block, 0, st, a); break;
+    case 4: hipLaunchKernelGGL((k_attn_partial<T, 4, FUSED>), grid, block, 0, st, a); break;
+    case 8: hipLaunchKernelGGL((k_attn_partial<T, 8, FUSED>), grid, block, 0, st, a); break;
     default: return hipErrorInvalidValue;
   }
-#undef CK_ATT
   if (n_split > 1)
-    hipLaunchKernelGGL(k_attn_merge<T>, dim3(dm.S * dm.Hq), dim3(D), 0, st, part, n_split, dm.G,
-                       dm.Hq, dm.Hkv, (T*)out);
+    hipLaunchKernelGGL(k_attn_merge<T>, dim3(dm.S * dm.Hq), dim3(D), 0, st, a.part, n_split, dm.G,
+                       dm.Hq, dm.Hkv, (T*)a.out);
   return hipGetLastError();
+}
+
+static AttnArgs common_args(const Dims& dm, const void* q, const void* K, const void* V,
+                            int idx_stride, int max_tokens, int64_t n_sink, int64_t recent_begin,
+                            int64_t recent_end, float softmax_scale, void* out, void* workspace) {
+  AttnArgs a = {};
+  a.q = q;
+  a.K = K;
+  a.V = V;
+  a.out = out;
+  a.part = reinterpret_cast<float*>(workspace);
+  a.idx_stride = idx_stride;
+  a.max_tokens = max_tokens;
+  a.Hq = dm.Hq;
+  a.Hkv = dm.Hkv;
+  a.C_cap = dm.C_cap;
+  a.N_cap = dm.N_cap;
+  a.n_sink = (int)n_sink;
+  a.recent_begin = recent_begin;
+  a.n_recent = (int)(recent_end > recent_begin ? recent_end - recent_begin : 0);
+  a.scale_log2e = softmax_scale * 1.4426950408889634f;
+  return a;
 }
 
 hipError_t launch_sparse_attn(const Dims& dm, const void* q, const void* K, const void* V,
@@ -261,11 +405,42 @@ hipError_t launch_sparse_attn(const Dims& dm, const void* q, const void* K, cons
                               int64_t max_total, int64_t n_sink, int64_t recent_begin,
                               int64_t recent_end, float softmax_scale, void* out, void* workspace,
                               hipStream_t st) {
-  if (dm.dtype == CK_BF16)
-    return launch_attn_t<bf16>(dm, q, K, V, token_idx, n_tokens, idx_stride, max_total, n_sink,
-                               recent_begin, recent_end, softmax_scale, out, workspace, st);
-  return launch_attn_t<float>(dm, q, K, V, token_idx, n_tokens, idx_stride, max_total, n_sink,
-                              recent_begin, recent_end, softmax_scale, out, workspace, st);
+  const int n_recent = (int)(recent_end > recent_begin ? recent_end - recent_begin : 0);
+  AttnArgs a = common_args(dm, q, K, V, idx_stride, (int)(max_total - n_sink - n_recent), n_sink,
+                           recent_begin, recent_end, softmax_scale, out, workspace);
+  a.token_idx = token_idx;
+  a.n_tokens = n_tokens;
+  if (dm.dtype == CK_BF16) return launch_attn_t<bf16, false>(dm, a, max_total, st);
+  return launch_attn_t<float, false>(dm, a, max_total, st);
+}
+
+hipError_t launch_decode_fused(const Dims& dm, const void* q, const void* K, const void* V,
+                               const void* centroids, const int32_t* sizes,
+                               const int32_t* offsets, const int32_t* sorted_idx, int n_clusters,
+                               int budget, uint32_t flags, int64_t n_sink, int64_t recent_begin,
+                               int64_t recent_end, float softmax_scale, float* scores,
+                               int32_t* sel_clusters, int32_t* n_sel_clusters,
+                               int32_t* n_sel_tokens, int32_t* token_idx, int idx_stride,
+                               int32_t* n_tokens, void* out, void* workspace, hipStream_t st) {
+  hipError_t e = launch_score(dm, q, centroids, n_clusters, scores, st);
+  if (e != hipSuccess) return e;
+  AttnArgs a = common_args(dm, q, K, V, idx_stride, budget, n_sink, recent_begin, recent_end,
+                           softmax_scale, out, workspace);
+  a.scores = scores;
+  a.sizes = sizes;
+  a.offsets = offsets;
+  a.sorted_idx = sorted_idx;
+  a.sel_clusters = sel_clusters;
+  a.n_sel_clusters = n_sel_clusters;
+  a.n_sel_tokens = n_sel_tokens;
+  a.token_idx_out = token_idx;
+  a.n_tokens_out = n_tokens;
+  a.n_clusters = n_clusters;
+  a.budget = budget;
+  a.trim = (int)(flags & CK_SEL_TRIM_LAST);
+  const int64_t max_total = (int64_t)budget + n_sink + a.n_recent;
+  if (dm.dtype == CK_BF16) return launch_attn_t<bf16, true>(dm, a, max_total, st);
+  return launch_attn_t<float, true>(dm, a, max_total, st);
 }
 
 }  // namespace ck

@@ -88,12 +88,29 @@ def test_argument_validation_without_a_device():
     expect(-4, cluster, lab=A + 4)
     expect(-1, cluster, sh=ck.Shape(1, 30, 8, 1000, 40))            # Hq not a multiple of Hkv
 
-    expect(-1, ck.ck_select_clusters, sh, A, A, A, 0, 10, 0, A, A, A)
-    expect(-1, ck.ck_select_clusters, sh, A, A, A, 41, 10, 0, A, A, A)
-    expect(-1, ck.ck_select_clusters, sh, A, A, A, 40, 0, 0, A, A, A)
-    expect(-1, ck.ck_select_clusters, sh, A, A, A, 40, 10, 7, A, A, A)
-    expect(-1, ck.ck_select_clusters, sh, None, A, A, 40, 10, 0, A, A, A)
-    expect(-4, ck.ck_select_clusters, sh, A, A + 8, A, 40, 10, 0, A, A, A)
+    expect(-1, ck.ck_select_clusters, sh, A, A, A, 0, 10, 0, A, A, A, A)
+    expect(-1, ck.ck_select_clusters, sh, A, A, A, 41, 10, 0, A, A, A, A)
+    expect(-1, ck.ck_select_clusters, sh, A, A, A, 40, 0, 0, A, A, A, A)
+    expect(-1, ck.ck_select_clusters, sh, A, A, A, 40, 10, 7, A, A, A, A)
+    expect(-1, ck.ck_select_clusters, sh, None, A, A, 40, 10, 0, A, A, A, A)
+    expect(-1, ck.ck_select_clusters, sh, A, A, A, 40, 10, 0, A, A, A, None)
+    expect(-4, ck.ck_select_clusters, sh, A, A + 8, A, 40, 10, 0, A, A, A, A)
+
+    def fused(**kw):
+        args = dict(q=A, K=A, V=A, cent=A, sizes=A, offs=A, sidx=A, nc=40, B=16, flags=0,
+                    scores=A, sel=A, nsel=A, ntok=A, idx=A, n=A, out=A, workspace=A)
+        args.update(kw)
+        ck.ck_decode_step(sh, args["q"], args["K"], args["V"], args["cent"], args["sizes"],
+                          args["offs"], args["sidx"], args["nc"], args["B"], args["flags"],
+                          args["scores"], args["sel"], args["nsel"], args["ntok"], args["idx"],
+                          args["n"], args["out"], workspace=args["workspace"])
+
+    expect(-1, fused, sidx=None)
+    expect(-1, fused, nc=41)
+    expect(-1, fused, B=0)
+    expect(-1, fused, flags=2)
+    expect(-3, fused, workspace=0)
+    expect(-4, fused, scores=A + 4)
 
     expect(-1, ck.ck_gather_indices, sh, A, A, A, A, 0, 0, A, A)
     expect(-1, ck.ck_gather_indices, sh, A, None, A, A, 16, 0, A, A)

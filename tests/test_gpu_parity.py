@@ -196,8 +196,8 @@ def oracle_tables(w, cfg, n_iter=4):
     return out
 
 
-def upload_tables(tabs, cfg, sh, budget, dtype=torch.bfloat16):
-    st = ck.ClusterState(sh, DEV, budget=budget)
+def upload_tables(tabs, cfg, sh, budget, dtype=torch.bfloat16, n_sink=0, max_recent=0):
+    st = ck.ClusterState(sh, DEV, budget=budget, n_sink=n_sink, max_recent=max_recent)
     for i, t in enumerate(tabs):
         s, h = divmod(i, cfg.Hkv)
         st.centroids[s, h, :cfg.C] = torch.from_numpy(t["mu"].astype(np.float32)).to(dtype).to(DEV)
@@ -208,9 +208,10 @@ def upload_tables(tabs, cfg, sh, budget, dtype=torch.bfloat16):
     return st
 
 
+@pytest.mark.parametrize("fused", [False, True])
 @pytest.mark.parametrize("Hq,Hkv,S", [(2, 2, 1), (8, 2, 2), (8, 1, 1)])
 @pytest.mark.parametrize("dtype", [ck.CK_BF16, ck.CK_F32])
-def test_select_gather_attention_vs_oracle(Hq, Hkv, S, dtype):
+def test_select_gather_attention_vs_oracle(Hq, Hkv, S, dtype, fused):
     cfg = small_cfg(1500, 50, 64, Hkv=Hkv, Hq=Hq, S=S, seed=3)
     w = MixtureWorkload(cfg, device=DEV)
     tabs = oracle_tables(w, cfg)
@@ -223,9 +224,9 @@ def test_select_gather_attention_vs_oracle(Hq, Hkv, S, dtype):
             sh = ck.Shape(S, Hq, Hkv, cfg.N, cfg.C, dtype=dtype)
             st = upload_tables(tabs, cfg, sh, budget, tdt)
             q = w.query().to(tdt)
-            scores = torch.zeros(S, Hkv, cfg.C, dtype=torch.float32, device=DEV)
-            out = ck.decode_step(st, q, K, V, flags=flags, scores=scores)
+            out = ck.decode_step(st, q, K, V, flags=flags, fused=fused)
             torch.cuda.synchronize()
+            scores = st.scores
             for i, t in enumerate(tabs):
                 s, h = divmod(i, Hkv)
                 qg = np64(q[s, h * G:(h + 1) * G])
@@ -279,14 +280,77 @@ def test_fig8_example_on_gpu():
                                               (ck.CK_SEL_TRIM_LAST, 1, [5], 1)]:
         st.budget = budget
         ck.ck_select_clusters(sh, q, st.centroids, st.sizes, C, budget, flags, st.sel_clusters,
-                              st.n_sel_clusters, st.n_sel_tokens)
+                              st.n_sel_clusters, st.n_sel_tokens, st.scores)
         ck.ck_gather_indices(sh, st.sel_clusters, st.n_sel_clusters, st.offsets, st.sorted_idx,
                              budget, flags, st.token_idx, st.n_tokens)
-        assert st.sel_clusters.flatten().tolist() == [2, 0, 1]
         assert int(st.n_sel_clusters) == want_sel
+        assert st.sel_clusters.flatten().tolist()[:want_sel] == [2, 0, 1][:want_sel]
         n = int(st.n_tokens)
         assert n == len(want_idx) == int(st.n_sel_tokens)
         assert st.token_idx.flatten()[:n].tolist() == want_idx
+
+
+def test_fused_decode_step_equals_three_calls():
+    """ck_decode_step against ck_select_clusters + ck_gather_indices +
+    ck_sparse_decode_attn on the same table, with sinks and a recent window."""
+    cfg = small_cfg(3000, 120, 128, Hkv=2, Hq=8, S=2, seed=9)
+    w = MixtureWorkload(cfg, device=DEV)
+    tabs = oracle_tables(w, cfg, n_iter=2)
+    sh = ck.Shape(cfg.S, cfg.Hq, cfg.Hkv, cfg.N, cfg.C)
+    for budget, flags, n_sink, recent in [(512, 0, 0, (0, 0)), (512, 1, 16, (2900, 3000)),
+                                          (100, 0, 4, (2990, 3000)), (3000, 1, 0, (0, 0)),
+                                          (37, 1, 0, (0, 0))]:
+        q = w.query()
+        res = []
+        for fused in (False, True):
+            st = upload_tables(tabs, cfg, sh, budget, n_sink=n_sink,
+                               max_recent=recent[1] - recent[0])
+            ck.decode_step(st, q, w.K, w.V, flags=flags, n_sink=n_sink, recent_begin=recent[0],
+                           recent_end=recent[1], fused=fused)
+            torch.cuda.synchronize()
+            res.append(st)
+        a, b = res
+        assert torch.equal(a.n_sel_clusters, b.n_sel_clusters)
+        assert torch.equal(a.n_sel_tokens, b.n_sel_tokens)
+        assert torch.equal(a.n_tokens, b.n_tokens)
+        assert torch.equal(a.scores, b.scores)
+        for s in range(cfg.S):
+            for h in range(cfg.Hkv):
+                ns, nt = int(a.n_sel_clusters[s, h]), int(a.n_tokens[s, h])
+                assert torch.equal(a.sel_clusters[s, h, :ns], b.sel_clusters[s, h, :ns])
+                assert torch.equal(a.token_idx[s, h, :nt], b.token_idx[s, h, :nt])
+        assert rel_err(np64(b.out), np64(a.out)) <= 2e-2
+
+
+def test_selection_with_degenerate_scores():
+    """All clusters score the same (zero query): the order is by cluster id, which
+    forces the rank-every-cluster path; also more clusters than one candidate list."""
+    N, C = 4096, 700
+    sh = ck.Shape(1, 4, 1, N, C)
+    rng = np.random.default_rng(5)
+    labels = rng.integers(0, C, N)
+    sizes, offsets, sidx = O.build_metadata(labels, C)
+    mu = O.round_to_bf16(rng.normal(size=(C, 128)))
+    K = torch.randn(1, 1, N, 128, device=DEV).to(torch.bfloat16)
+    V = torch.randn(1, 1, N, 128, device=DEV).to(torch.bfloat16)
+    for qscale in (0.0, 1.0):
+        q = (qscale * torch.randn(1, 4, 128)).to(torch.bfloat16).to(DEV)
+        for budget, flags in [(300, 0), (300, 1), (5000, 0), (5000, 1), (3, 0)]:
+            for fused in (False, True):
+                st = ck.ClusterState(sh, DEV, budget=budget)
+                st.centroids[0, 0] = bf16_dev(mu)
+                st.sizes[0, 0] = i32_dev(sizes)
+                st.offsets[0, 0] = i32_dev(offsets)
+                st.sorted_idx[0, 0] = i32_dev(sidx)
+                st.n_clusters = C
+                ck.decode_step(st, q, K, V, flags=flags, fused=fused)
+                torch.cuda.synchronize()
+                r = O.decode_step(np64(q[0]), np64(K[0, 0]), np64(V[0, 0]), mu, sizes, offsets,
+                                  sidx, budget, flags)
+                if qscale == 0.0 or not O.selection_near_tie(r["scores"], r["order"], r["n_sel"]):
+                    n = int(st.n_tokens)
+                    assert int(st.n_sel_clusters) == r["n_sel"] and n == r["n_tok"]
+                    assert np.array_equal(st.token_idx[0, 0, :n].cpu().numpy(), r["idx"])
 
 
 # ---------------------------------------------------------------- attention alone
@@ -362,8 +426,7 @@ def test_llama3_8b_layer_sampled():
     st = ck.ClusterState(sh, DEV, budget=cfg.B)
     st.cluster(w.K, init.to(DEV), 0, cfg.N, cfg.C, cfg.n_iter)
     q = w.query()
-    scores = torch.zeros(cfg.S, cfg.Hkv, cfg.C, dtype=torch.float32, device=DEV)
-    out = ck.decode_step(st, q, w.K, w.V, scores=scores)
+    out = ck.decode_step(st, q, w.K, w.V)
     torch.cuda.synchronize()
     rng = np.random.default_rng(0)
     flagged = 0
