@@ -34,6 +34,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-batch8", action="store_true",
                     help="skip the extra decode-only measurement at batch 8, B=2048")
+    ap.add_argument("--full-depth", action="store_true",
+                    help="also run all 32 layers x 8 sequences of the full-depth configuration "
+                         "as one batch of 2048 head-problems (needs ~36 GiB of HBM)")
     return ap.parse_args()
 
 
@@ -77,9 +80,10 @@ def decode_bytes(cfg, st, C):
                 mean_tokens=float(n_tok.mean()))
 
 
-def cpu_baseline(cfg, w, init, q):
-    """The oracle, as it stands, on the host cores: one of the head-problems of the
-    workload, full K-means plus one decode step."""
+def cpu_baseline(cfg, w, init, q, budget_s=20.0):
+    """The oracle, as it stands, on the host cores: whole head-problems of the
+    workload (full K-means + metadata + one decode step each) until about
+    budget_s seconds of CPU time are spent."""
     import numpy as np
     from oracle import clusterkv_oracle as O
     try:
@@ -87,19 +91,69 @@ def cpu_baseline(cfg, w, init, q):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = os.cpu_count()
-    keys = w.K[0, 0, :cfg.N].float().cpu().numpy().astype(np.float64)
-    vals = w.V[0, 0, :cfg.N].float().cpu().numpy().astype(np.float64)
-    qg = q[0, :cfg.G].float().cpu().numpy().astype(np.float64)
-    t0 = time.perf_counter()
-    mu, labels, sizes, _ = O.kmeans(keys, init[0, 0].numpy(), cfg.n_iter, "bf16")
-    sizes, offsets, sidx = O.build_metadata(labels, cfg.C)
-    t1 = time.perf_counter()
-    O.decode_step(qg, keys, vals, O.round_to_bf16(mu), sizes, offsets, sidx, cfg.B)
-    t2 = time.perf_counter()
-    return {"value": cfg.N / (t2 - t0), "unit": "keys/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"1 of {cfg.S * cfg.Hkv} head-problems of {cfg.name}: {cfg.n_iter}-iteration "
-                      f"K-means over {cfg.N} keys (C={cfg.C}) + metadata + one decode step",
-            "kmeans_s": t1 - t0, "decode_step_s": t2 - t1}
+    done = 0
+    t_km = t_dec = 0.0
+    t_start = time.perf_counter()
+    for hp in range(cfg.S * cfg.Hkv):
+        s, h = divmod(hp, cfg.Hkv)
+        keys = w.K[s, h, :cfg.N].float().cpu().numpy().astype(np.float64)
+        vals = w.V[s, h, :cfg.N].float().cpu().numpy().astype(np.float64)
+        qg = q[s, h * cfg.G:(h + 1) * cfg.G].float().cpu().numpy().astype(np.float64)
+        t0 = time.perf_counter()
+        mu, labels, sizes, _ = O.kmeans(keys, init[s, h].numpy(), cfg.n_iter, "bf16")
+        sizes, offsets, sidx = O.build_metadata(labels, cfg.C)
+        t1 = time.perf_counter()
+        O.decode_step(qg, keys, vals, O.round_to_bf16(mu), sizes, offsets, sidx, cfg.B)
+        t2 = time.perf_counter()
+        t_km += t1 - t0
+        t_dec += t2 - t1
+        done += 1
+        if time.perf_counter() - t_start > budget_s:
+            break
+    return {"value": done * cfg.N / (t_km + t_dec), "unit": "keys/s", "cores": int(threads),
+            "kind": "oracle",
+            "sample": f"{done} of {cfg.S * cfg.Hkv} head-problems of {cfg.name}: {cfg.n_iter}-iteration "
+                      f"K-means over {cfg.N} keys (C={cfg.C}) + metadata + one decode step each",
+            "kmeans_s_per_head_problem": t_km / done,
+            "decode_step_s_per_head_problem": t_dec / done}
+
+
+def graph_ms(fn, reps):
+    """fn captured once into a HIP graph; average replay time."""
+    import torch
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for _ in range(3):
+            fn()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        fn()
+    for _ in range(5):
+        g.replay()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        g.replay()
+    b.record()
+    b.synchronize()
+    return a.elapsed_time(b) / reps
+
+
+def read_traffic(kernel_tag):
+    """HBM bytes per launch of a kernel as measured with rocprofv3 --pmc
+    (FETCH_SIZE + WRITE_SIZE, calibrated), from the committed summary if present."""
+    path = os.path.join(ROOT, "profiles", f"{kernel_tag}_pmc.md")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
 
 
 def main():
@@ -154,6 +208,7 @@ def main():
     reps = max(args.steps, 10)
     cluster_ms = event_ms(cluster, reps)
     decode_ms = event_ms(decode, 10 * reps)
+    decode_graph_ms = graph_ms(decode, 10 * reps)
     db = decode_bytes(cfg, st, cfg.C)
 
     # dominant kernel: the MFMA assignment, one launch at a time
@@ -191,15 +246,18 @@ def main():
         "kmeans_keys_per_s": keys_per_step / (cluster_ms * 1e-3),
         "kmeans_ms": cluster_ms,
         "decode_us_per_layer": decode_ms * 1e3,
+        "decode_us_per_layer_hipgraph": decode_graph_ms * 1e3,
         "recalled_kv_GBps": db["kv"] / (decode_ms * 1e-3) / 1e9,
         "recalled_tokens_mean": db["mean_tokens"],
         "roofline": {"kernel": "k_assign (bf16 MFMA assignment, one launch = one K-means "
                                "iteration over all head-problems)",
                      "bound": "mfma", "achieved": achieved_tflops, "peak": PEAK_BF16_MFMA_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved_tflops / PEAK_BF16_MFMA_TFLOPS,
-                     "traffic": None, "flops_per_launch": assign_flops,
+                     "traffic": read_traffic("k_assign_" + cfg.name),
+                     "flops_per_launch": assign_flops,
                      "launch_ms_avg": a_avg, "launch_ms_median": a_med, "launch_ms_min": a_min},
-        "roofline_decode": {"kernels": "k_select + k_gather + k_attn_partial + k_attn_merge",
+        "roofline_decode": {"kernels": "ck_decode_step = k_score + k_attn_partial(fused select/"
+                                       "gather) + k_attn_merge",
                             "bound": "hbm", "achieved": db["total"] / (decode_ms * 1e-3) / 1e9,
                             "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                             "frac": db["total"] / (decode_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS,
@@ -209,24 +267,36 @@ def main():
     }
 
     if not args.no_batch8:
-        result["decode_batch8_B2048"] = batch8_decode(reps)
+        result["decode_batch8_B2048"] = big_decode(reps, layers=1)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, w, init, q)
+    if args.full_depth:
+        del w, st
+        torch.cuda.empty_cache()
+        result["decode_full_depth_32layers"] = big_decode(max(reps // 2, 5), layers=32)
+    # a plain copy of known size: lets a rocprofv3 --pmc run of this script calibrate
+    # FETCH_SIZE / WRITE_SIZE (256 MiB read + 256 MiB written)
+    src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
     print(json.dumps(result))
 
 
-def batch8_decode(reps):
-    """Decode-only measurement on one layer of the full-depth configuration
-    (8 sequences, B = 2048), where a step moves enough bytes for the HBM roofline
-    to mean something."""
+def big_decode(reps, layers):
+    """Decode-only measurement on the full-depth configuration (8 sequences,
+    B = 2048), where a step moves enough bytes for the HBM roofline to mean
+    something: one layer (64 head-problems), or all 32 layers as ONE batch of 2048
+    head-problems (an upper bound: a real model runs its layers one after another)."""
     import torch
     import paper_2412_03213_amd as ck
     from ck_synth import Config, MixtureWorkload, get_config, sample_init_indices
     c2 = get_config(2)
-    cfg = Config("full_depth_one_layer", 1, c2.S, c2.Hkv, c2.Hq, c2.d, c2.N, c2.M, c2.C,
-                 c2.n_iter, c2.B, c2.seed)
+    cfg = Config(f"full_depth_{layers}_layers", 1, c2.S * layers, c2.Hkv, c2.Hq, c2.d, c2.N, c2.M,
+                 c2.C, c2.n_iter, c2.B, c2.seed)
     dev = "cuda:0"
     w = MixtureWorkload(cfg, device=dev)
+    w.token_center = None
     init = sample_init_indices(w.K, cfg.C, cfg.seed).to(dev)
     sh = ck.Shape(cfg.S, cfg.Hq, cfg.Hkv, cfg.N, cfg.C)
     st = ck.ClusterState(sh, dev, budget=cfg.B)
@@ -240,6 +310,7 @@ def batch8_decode(reps):
     for _ in range(5):
         decode()
     ms = event_ms(decode, 10 * reps)
+    ms_graph = graph_ms(decode, 10 * reps)
     db = decode_bytes(cfg, st, cfg.C)
 
     def attn():
@@ -247,10 +318,14 @@ def batch8_decode(reps):
                                  workspace=st.attn_ws)
 
     at_avg, at_med, at_min = per_launch_ms(attn, 10 * reps)
-    gbps = db["total"] / (ms * 1e-3) / 1e9
-    return {"workload": "one layer of full_depth_32layers_b8 (S=8, N=32768, C=400, B=2048)",
-            "decode_us_per_layer": ms * 1e3, "bytes_per_step": db["total"],
-            "recalled_kv_GBps": db["kv"] / (ms * 1e-3) / 1e9,
+    best = min(ms, ms_graph)
+    gbps = db["total"] / (best * 1e-3) / 1e9
+    return {"workload": f"{layers} layer(s) of full_depth_32layers_b8 as one batch: "
+                        f"{cfg.S * cfg.Hkv} head-problems, N=32768, C=400, B=2048",
+            "decode_us_per_step": ms * 1e3, "decode_us_per_step_hipgraph": ms_graph * 1e3,
+            "decode_us_per_layer": best * 1e3 / layers,
+            "bytes_per_step": db["total"],
+            "recalled_kv_GBps": db["kv"] / (best * 1e-3) / 1e9,
             "recalled_tokens_mean": db["mean_tokens"],
             "roofline": {"bound": "hbm", "achieved": gbps, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                          "frac": gbps / PEAK_HBM_GBPS},
