@@ -143,6 +143,36 @@ def graph_ms(fn, reps):
     return a.elapsed_time(b) / reps
 
 
+def measured_peaks(dev):
+    """What the chip sustains in the simplest possible kernels: a register-only bf16
+    MFMA loop (constant operands, so it runs at the full clock) and a device copy."""
+    import torch
+    import paper_2412_03213_amd as ck
+    sink = torch.zeros(4, device=dev)
+    ck.ck_probe_mfma_bf16(1024, 200, sink)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    fl = ck.ck_probe_mfma_bf16(1024, 4000, sink)
+    b.record()
+    b.synchronize()
+    mfma = fl / (a.elapsed_time(b) * 1e-3) / 1e12
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    a.record()
+    for _ in range(5):
+        dst.copy_(src)
+    b.record()
+    b.synchronize()
+    copy = 5 * 2 * src.numel() / (a.elapsed_time(b) * 1e-3) / 1e9
+    return {"mfma_bf16_TFLOPs_register_loop": mfma, "copy_GBps_read_plus_write": copy,
+            "note": "under the assignment kernel's real data the shader clock drops from "
+                    "~2.39 GHz to ~1.99 GHz (rocm-smi), so ~83% of the MFMA figure is the "
+                    "ceiling that kernel can see"}
+
+
 def read_traffic(kernel_tag):
     """HBM bytes per launch of a kernel as measured with rocprofv3 --pmc
     (FETCH_SIZE + WRITE_SIZE, calibrated), from the committed summary if present."""
@@ -223,6 +253,7 @@ def main():
     for _ in range(3):
         assign()
     a_avg, a_med, a_min = per_launch_ms(assign, 10 * reps)
+    a_train = event_ms(assign, 10 * reps)       # back-to-back launches, one event pair around all
     assign_flops = 2.0 * HP * cfg.N * cfg.C * cfg.d
     achieved_tflops = assign_flops / (a_avg * 1e-3) / 1e12
 
@@ -255,7 +286,8 @@ def main():
                      "unit": "TFLOP/s", "frac": achieved_tflops / PEAK_BF16_MFMA_TFLOPS,
                      "traffic": read_traffic("k_assign_" + cfg.name),
                      "flops_per_launch": assign_flops,
-                     "launch_ms_avg": a_avg, "launch_ms_median": a_med, "launch_ms_min": a_min},
+                     "launch_ms_avg": a_avg, "launch_ms_median": a_med, "launch_ms_min": a_min,
+                     "launch_ms_back_to_back": a_train},
         "roofline_decode": {"kernels": "ck_decode_step = k_score + k_attn_partial(fused select/"
                                        "gather) + k_attn_merge",
                             "bound": "hbm", "achieved": db["total"] / (decode_ms * 1e-3) / 1e9,
@@ -266,6 +298,7 @@ def main():
                             "note": "batch 1: 8 head-problems, launch-latency bound"},
     }
 
+    result["measured_peaks"] = measured_peaks(dev)
     if not args.no_batch8:
         result["decode_batch8_B2048"] = big_decode(reps, layers=1)
     if not args.no_cpu_baseline:

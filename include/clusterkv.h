@@ -238,6 +238,17 @@ int ck_decode_step(const ck_shape* sh, const void* q, const void* K, const void*
                    int32_t* n_tokens, void* out, void* workspace, size_t workspace_bytes,
                    void* stream);
 
+/*
+ * Measurement aid, not part of the method: a register-only loop of
+ * v_mfma_f32_32x32x16_bf16 (the instruction the assignment step of Section III-B
+ * runs on) over n_workgroups workgroups of 4 wavefronts, `iters` x 16 MFMAs per
+ * wavefront.  *flops [host] receives the floating-point operations of the launch,
+ * so that flops / elapsed time is the matrix throughput the chip sustains at its
+ * real clocks.  sink [dev]: at least one float, never written in practice.
+ */
+int ck_probe_mfma_bf16(int32_t n_workgroups, int32_t iters, float* sink, double* flops,
+                       void* stream);
+
 #ifdef __cplusplus
 }
 #endif

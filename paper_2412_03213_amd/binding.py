@@ -22,7 +22,8 @@ LIB_PATH = os.path.join(_PKG, "libclusterkv.so")
 
 EXPORTS = ("ck_version", "ck_strerror", "ck_last_error_detail", "ck_workspace_bytes",
            "ck_cluster_keys", "ck_kmeans_assign", "ck_build_metadata", "ck_kmeans_update",
-           "ck_select_clusters", "ck_gather_indices", "ck_sparse_decode_attn", "ck_decode_step")
+           "ck_select_clusters", "ck_gather_indices", "ck_sparse_decode_attn", "ck_decode_step",
+           "ck_probe_mfma_bf16")
 
 
 class ClusterKVError(RuntimeError):
@@ -98,6 +99,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.ck_decode_step.restype = ctypes.c_int
     lib.ck_decode_step.argtypes = [SH, P, P, P, P, P, P, P, I32, I32, U32, I64, I64, I64, F,
                                    P, P, P, P, P, I32, P, P, P, SZ, P]
+    lib.ck_probe_mfma_bf16.restype = ctypes.c_int
+    lib.ck_probe_mfma_bf16.argtypes = [I32, I32, P, ctypes.POINTER(ctypes.c_double), P]
     _lib = lib
     return lib
 
@@ -222,6 +225,15 @@ def ck_sparse_decode_attn(sh: Shape, q, K, V, token_idx, n_tokens, max_tokens, o
                                      workspace.numel() if isinstance(workspace, torch.Tensor)
                                      else 0, _stream(q)))
     return workspace
+
+
+def ck_probe_mfma_bf16(n_workgroups: int, iters: int, sink) -> float:
+    """Enqueue the MFMA probe; returns the flops of the launch."""
+    lib = load_library()
+    fl = ctypes.c_double(0.0)
+    _check(lib.ck_probe_mfma_bf16(n_workgroups, iters, _ptr(sink), ctypes.byref(fl),
+                                  _stream(sink)))
+    return fl.value
 
 
 class ClusterState:

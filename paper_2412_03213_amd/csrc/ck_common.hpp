@@ -141,6 +141,7 @@ hipError_t launch_gather(const Dims& dm, const int32_t* sel_clusters,
                          const int32_t* n_sel_clusters, const int32_t* offsets,
                          const int32_t* sorted_idx, int budget, uint32_t flags,
                          int32_t* token_idx, int idx_stride, int32_t* n_tokens, hipStream_t st);
+hipError_t launch_probe_mfma(int n_workgroups, int iters, float* sink, hipStream_t st);
 int attn_num_splits(const Dims& dm, int64_t max_total);
 size_t attn_workspace_bytes(const Dims& dm, int64_t max_total);
 hipError_t launch_sparse_attn(const Dims& dm, const void* q, const void* K, const void* V,
