@@ -38,6 +38,7 @@ constexpr int SELP_ITEMS = CK_MAX_CLUSTERS / SELP_THREADS;
 struct SelectLds {
   uint32_t key[CK_MAX_CLUSTERS];   // ~ordered(score): ascending key = descending score
   int ssz[CK_MAX_CLUSTERS];        // size per cluster id
+  int soff[CK_MAX_CLUSTERS];       // offsets[cluster] per cluster id (when offsets are given)
   int ord[CK_MAX_CLUSTERS];        // cluster id per sorted position
   int cum[CK_MAX_CLUSTERS];        // inclusive prefix sum of sizes per sorted position
   int cbeg[SELP_MAX_CAND];         // offsets[cluster] per sorted position (candidate path only)
@@ -69,6 +70,19 @@ __device__ __forceinline__ void select_prefix(SelectLds& L, const float* __restr
     const int c = tid + i * SELP_THREADS;
     sc[i] = c < C ? scores[c] : 0.f;
     sz[i] = c < C ? sizes[c] : 0;
+  }
+  if (offsets) {                       // same round trip as the scores: no dependent load later
+    int of[SELP_ITEMS];
+#pragma unroll
+    for (int i = 0; i < SELP_ITEMS; ++i) {
+      const int c = tid + i * SELP_THREADS;
+      of[i] = c < C ? offsets[c] : 0;
+    }
+#pragma unroll
+    for (int i = 0; i < SELP_ITEMS; ++i) {
+      const int c = tid + i * SELP_THREADS;
+      if (c < C) L.soff[c] = of[i];
+    }
   }
 #pragma unroll
   for (int i = 0; i < SELP_ITEMS; ++i) {
@@ -181,7 +195,7 @@ __device__ __forceinline__ void select_prefix(SelectLds& L, const float* __restr
     for (int i = tid; i < m; i += SELP_THREADS) {
       const int c = L.cand[i];
       const uint32_t kc = L.key[c];
-      const int ob = offsets ? offsets[c] : 0;
+      const int ob = offsets ? L.soff[c] : 0;
       int rank = 0;
       for (int j = 0; j < m; ++j) {
         const int cj = L.cand[j];

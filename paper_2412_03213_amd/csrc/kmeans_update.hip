@@ -132,62 +132,78 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_sort_scan(
 
 // Pass 3: exclusive scan of the sizes -> offsets (every workgroup recomputes it in
 // LDS, the first one of a head-problem stores it), then the stable scatter of the
-// token rows to their sorted positions, one chunk per wavefront.
+// token rows of ONE chunk to their sorted positions.  The four wavefronts each rank a
+// quarter of the chunk; per-wavefront label counts in LDS order the quarters.
 constexpr int OFF_ITEMS = CK_MAX_CLUSTERS / SORT_THREADS;   // 8 clusters per thread
+constexpr int SCAT_ROUNDS = 2;                              // chunk_tokens <= 4 * 2 * 64
 __global__ __launch_bounds__(SORT_THREADS) void k_sort_scatter(
     const int32_t* __restrict__ labels, int64_t N_cap, int64_t tok_begin, int64_t tok_count,
     int C_cap, int c_begin, int c_count, int label_bits, int n_chunks, int chunk_tokens,
     const int32_t* __restrict__ chunk_hist, const int32_t* __restrict__ sizes,
     int32_t* __restrict__ offsets, int32_t* __restrict__ sorted_idx) {
-  extern __shared__ int lds_hist[];                     // [c_count] offsets + [4][c_count]
+  extern __shared__ int lds_hist[];                     // [c_count] positions + [4][c_count] counts
   __shared__ int tmp[SORT_THREADS / WAVE + 1];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hp = blockIdx.y;
+  const int chunk = blockIdx.x;
   int* offs = lds_hist;
+  int* cnt = lds_hist + c_count;
   int32_t* off_g = offsets + (int64_t)hp * (C_cap + 1);
   const int base0 = c_begin == 0 ? 0 : off_g[c_begin];
+  const int32_t* cbase = chunk_hist + ((int64_t)hp * n_chunks + chunk) * c_count;
   {
     const int32_t* sz = sizes + (int64_t)hp * C_cap + c_begin;
-    int v[OFF_ITEMS], own[OFF_ITEMS];
+    int v[OFF_ITEMS], own[OFF_ITEMS], cb[OFF_ITEMS];
 #pragma unroll
     for (int i = 0; i < OFF_ITEMS; ++i) {
       const int c = tid * OFF_ITEMS + i;
       own[i] = v[i] = c < c_count ? sz[c] : 0;
+      cb[i] = c < c_count ? cbase[c] : 0;
     }
     block_inclusive_scan<OFF_ITEMS>(v, tmp);
 #pragma unroll
     for (int i = 0; i < OFF_ITEMS; ++i) {
       const int c = tid * OFF_ITEMS + i;
       if (c < c_count) {
-        offs[c] = base0 + v[i] - own[i];
-        if (blockIdx.x == 0) off_g[c_begin + c + 1] = base0 + v[i];
+        offs[c] = base0 + v[i] - own[i] + cb[i];        // first position of this chunk's tokens
+        if (chunk == 0) off_g[c_begin + c + 1] = base0 + v[i];
       }
     }
-    if (blockIdx.x == 0 && tid == 0 && c_begin == 0) off_g[0] = 0;
+    if (chunk == 0 && tid == 0 && c_begin == 0) off_g[0] = 0;
   }
+  for (int i = tid; i < 4 * c_count; i += SORT_THREADS) cnt[i] = 0;
   __syncthreads();
-  const int chunk = blockIdx.x * 4 + wave;
-  if (chunk >= n_chunks) return;                        // no block barriers below
-  volatile int* next = lds_hist + (1 + wave) * c_count;  // next free position per cluster
-  const int32_t* base = chunk_hist + ((int64_t)hp * n_chunks + chunk) * c_count;
-  for (int c = lane; c < c_count; c += WAVE) next[c] = offs[c] + base[c];
-  __builtin_amdgcn_wave_barrier();
+
+  const int per_wave = chunk_tokens / 4;
   const int32_t* lab = labels + (int64_t)hp * N_cap + tok_begin;
-  int32_t* out = sorted_idx + (int64_t)hp * N_cap;
   const uint64_t lt = ((uint64_t)1 << lane) - 1;
-  for (int r = 0; r < chunk_tokens / WAVE; ++r) {
-    const int64_t t = (int64_t)chunk * chunk_tokens + r * WAVE + lane;
-    const bool valid = t < tok_count;
+  volatile int* mine = cnt + wave * c_count;
+  int lbl[SCAT_ROUNDS], rank[SCAT_ROUNDS];
+  int64_t tok[SCAT_ROUNDS];
+#pragma unroll
+  for (int r = 0; r < SCAT_ROUNDS; ++r) {
+    const int in_wave = r * WAVE + lane;
+    const int64_t t = (int64_t)chunk * chunk_tokens + wave * per_wave + in_wave;
+    const bool valid = in_wave < per_wave && t < tok_count;
     int l = valid ? lab[t] - c_begin : 0;
     l = l < 0 ? 0 : (l >= c_count ? c_count - 1 : l);
     const uint64_t peers = same_label_mask(l, valid, label_bits);
-    const int first = next[l];
+    const int before = mine[l];
     __builtin_amdgcn_wave_barrier();
-    if (valid) {
-      const int64_t pos = first + __popcll(peers & lt);
-      if (pos >= 0 && pos < N_cap) out[pos] = (int32_t)(tok_begin + t);
-      if ((peers & lt) == 0) next[l] = first + __popcll(peers);
+    if (valid && (peers & lt) == 0) mine[l] = before + __popcll(peers);
+    __builtin_amdgcn_wave_barrier();
+    lbl[r] = l;
+    rank[r] = before + __popcll(peers & lt);
+    tok[r] = valid ? t : -1;
+  }
+  __syncthreads();
+  int32_t* out = sorted_idx + (int64_t)hp * N_cap;
+#pragma unroll
+  for (int r = 0; r < SCAT_ROUNDS; ++r) {
+    if (tok[r] >= 0) {
+      int pos = offs[lbl[r]] + rank[r];
+      for (int w = 0; w < wave; ++w) pos += cnt[w * c_count + lbl[r]];
+      if (pos >= 0 && pos < N_cap) out[pos] = (int32_t)(tok_begin + tok[r]);
     }
-    __builtin_amdgcn_wave_barrier();
   }
 }
 
@@ -206,7 +222,7 @@ hipError_t launch_metadata(const Dims& dm, const int32_t* labels, int64_t tok_be
                        n_chunks, chunk_tokens, chunk_hist);
   hipLaunchKernelGGL(k_sort_scan, dim3((c_count + 63) / 64, dm.HP), dim3(SCAN_THREADS), 0, st,
                      chunk_hist, n_chunks, dm.C_cap, c_begin, c_count, sizes);
-  hipLaunchKernelGGL(k_sort_scatter, grid, dim3(SORT_THREADS),
+  hipLaunchKernelGGL(k_sort_scatter, dim3(n_chunks, dm.HP), dim3(SORT_THREADS),
                      (size_t)5 * c_count * sizeof(int), st, labels, dm.N_cap, tok_begin, tok_count,
                      dm.C_cap, c_begin, c_count, label_bits, n_chunks, chunk_tokens, chunk_hist,
                      sizes, offsets, sorted_idx);

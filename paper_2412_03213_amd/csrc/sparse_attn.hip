@@ -117,7 +117,7 @@ __global__ __launch_bounds__(ATT_THREADS) void k_attn_partial(const AttnArgs a) 
       }
     }
     rows = reinterpret_cast<int*>(L.key);               // key + ssz: free after the ranking
-    red = reinterpret_cast<float*>(L.ord);              // ord..cand: free after the rows are known
+    red = reinterpret_cast<float*>(L.ord);              // ord, cum, cbeg, cand: free once the rows are known
   } else {
     rows = lds.rows;
     red = lds.red;
@@ -151,7 +151,7 @@ __global__ __launch_bounds__(ATT_THREADS) void k_attn_partial(const AttnArgs a) 
         const int size = L.cum[lo] - prev;
         int take = a.budget - prev;                     // a cut cluster keeps its trailing entries
         take = take > size ? size : take;
-        const int beg = L.full_rank ? a.offsets[(int64_t)hp * (a.C_cap + 1) + c] : L.cbeg[lo];
+        const int beg = L.full_rank ? L.soff[c] : L.cbeg[lo];
         int64_t src = (int64_t)beg + (size - take) + (qpos - prev);
         src = src < 0 ? 0 : (src >= a.N_cap ? a.N_cap - 1 : src);
         row = a.sorted_idx[(int64_t)hp * a.N_cap + src];
