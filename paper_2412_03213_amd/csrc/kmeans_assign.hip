@@ -33,31 +33,6 @@ __global__ __launch_bounds__(ASSIGN_THREADS, WAVES_PER_SIMD) void k_assign(
   const bf16* Khp = K + (int64_t)hp * N_cap * D;
   const bf16* Mhp = mu_hat + (int64_t)hp * c_count * D;
 
-  // ---- keys of this wavefront into registers, in B-operand layout ----
-  const int64_t wave_tok0 = ((int64_t)blockIdx.x * 4 + wave) * (NKB * 32);
-  bf16x8 bk[NKB][8];
-#pragma unroll
-  for (int kb = 0; kb < NKB; ++kb) {
-    int64_t t = wave_tok0 + kb * 32 + col;
-    if (t >= tok_count) t = tok_count - 1;            // clamp: result is discarded
-    const bf16* row = Khp + (tok_begin + t) * D + half * 8;
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) bk[kb][kk] = *reinterpret_cast<const bf16x8*>(row + kk * 16);
-  }
-
-  // Running maximum per key block as a "packed" float: the low 4 mantissa bits of
-  // every similarity are replaced by 15 - (accumulator slot), so one v_max3 chain
-  // finds value and slot together and equal values resolve to the lower centroid.
-  // The truncation moves a similarity by < 2^-19 relative, far inside the 1e-4
-  // cosine near-tie band in which labels may legitimately differ.
-  float bestp[NKB];
-  int btile[NKB];
-#pragma unroll
-  for (int kb = 0; kb < NKB; ++kb) {
-    bestp[kb] = -INFINITY;
-    btile[kb] = 0;
-  }
-
   const int n_chunks = (c_count + CHUNK_ROWS - 1) / CHUNK_ROWS;
   uint4 stage[4];
   // chunk = 64 rows x 256 B = 1024 segments of 16 B; thread handles 4 of them
@@ -79,8 +54,43 @@ __global__ __launch_bounds__(ASSIGN_THREADS, WAVES_PER_SIMD) void k_assign(
       *reinterpret_cast<uint4*>(&lds[buf][(seg >> 4) * LDS_ROW + (seg & 15) * 8]) = stage[i];
     }
   };
-
+  // first centroid chunk ahead of the keys, so that it does not queue behind them
   fetch(0);
+
+  // ---- keys of this wavefront into registers, in B-operand layout ----
+  // Issued fragment-major (all key blocks' fragment 0, then fragment 1, ...): the first
+  // tile's MFMAs then start as soon as the first few loads have landed and follow the
+  // arriving data instead of waiting for all of it.
+  const int64_t wave_tok0 = ((int64_t)blockIdx.x * 4 + wave) * (NKB * 32);
+  bf16x8 bk[NKB][8];
+  {
+    const bf16* rows[NKB];
+#pragma unroll
+    for (int kb = 0; kb < NKB; ++kb) {
+      int64_t t = wave_tok0 + kb * 32 + col;
+      if (t >= tok_count) t = tok_count - 1;            // clamp: result is discarded
+      rows[kb] = Khp + (tok_begin + t) * D + half * 8;
+    }
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk)
+#pragma unroll
+      for (int kb = 0; kb < NKB; ++kb)
+        bk[kb][kk] = *reinterpret_cast<const bf16x8*>(rows[kb] + kk * 16);
+  }
+
+  // Running maximum per key block as a "packed" float: the low 4 mantissa bits of
+  // every similarity are replaced by 15 - (accumulator slot), so one v_max3 chain
+  // finds value and slot together and equal values resolve to the lower centroid.
+  // The truncation moves a similarity by < 2^-19 relative, far inside the 1e-4
+  // cosine near-tie band in which labels may legitimately differ.
+  float bestp[NKB];
+  int btile[NKB];
+#pragma unroll
+  for (int kb = 0; kb < NKB; ++kb) {
+    bestp[kb] = -INFINITY;
+    btile[kb] = 0;
+  }
+
   stash(0);
   __syncthreads();
 
