@@ -36,6 +36,8 @@ def parse():
                     help="skip the extra decode-only measurement at batch 8, B=2048")
     ap.add_argument("--no-incremental", action="store_true",
                     help="skip the 1024-step decode loop with incremental clustering (batch 16)")
+    ap.add_argument("--no-long-context", action="store_true",
+                    help="skip the 128k-context leg (C=1600: K-means + one decode step)")
     ap.add_argument("--full-depth", action="store_true",
                     help="also run all 32 layers x 8 sequences of the full-depth configuration "
                          "as one batch of 2048 head-problems (needs ~36 GiB of HBM)")
@@ -306,6 +308,8 @@ def main():
     result["measured_peaks"] = measured_peaks(dev)
     if not args.no_batch8:
         result["decode_batch8_B2048"] = big_decode(reps, layers=1)
+    if not args.no_long_context:
+        result["long_context_128k"] = long_context(reps)
     if not args.no_incremental:
         result["incremental_decode_b16"] = incremental_decode()
     if not args.no_cpu_baseline:
@@ -321,6 +325,58 @@ def main():
     dst.copy_(src)
     torch.cuda.synchronize()
     print(json.dumps(result))
+
+
+def long_context(reps):
+    """The 128k-context configuration (C = 1600 clusters, B = 2048): K-means, the
+    assignment kernel's MFMA fraction at this cluster count, and one decode step."""
+    import torch
+    import paper_2412_03213_amd as ck
+    from ck_synth import MixtureWorkload, get_config, sample_init_indices
+    cfg = get_config(3)
+    dev = "cuda:0"
+    w = MixtureWorkload(cfg, device=dev)
+    w.token_center = None
+    init = sample_init_indices(w.K, cfg.C, cfg.seed).to(dev)
+    sh = ck.Shape(cfg.S, cfg.Hq, cfg.Hkv, cfg.N, cfg.C)
+    st = ck.ClusterState(sh, dev, budget=cfg.B)
+    HP = cfg.S * cfg.Hkv
+
+    def cluster():
+        st.n_clusters = 0
+        st.cluster(w.K, init, 0, cfg.N, cfg.C, cfg.n_iter)
+
+    cluster()
+    km = event_ms(cluster, 3)
+    mu_hat = st.cluster_ws[:HP * cfg.C * cfg.d * 2].view(torch.bfloat16).view(
+        cfg.S, cfg.Hkv, cfg.C, cfg.d)
+    labels2 = torch.empty_like(st.labels)
+
+    def assign():
+        ck.ck_kmeans_assign(sh, w.K, 0, cfg.N, mu_hat, 0, cfg.C, labels2)
+
+    for _ in range(3):
+        assign()
+    a_ms = event_ms(assign, 2 * reps)
+    flops = 2.0 * HP * cfg.N * cfg.C * cfg.d
+    q = w.query()
+
+    def decode():
+        ck.decode_step(st, q, w.K, w.V)
+
+    for _ in range(5):
+        decode()
+    d_ms = event_ms(decode, 10 * reps)
+    db = decode_bytes(cfg, st, cfg.C)
+    tf = flops / (a_ms * 1e-3) / 1e12
+    return {"workload": f"{cfg.name}: N={cfg.N}, C={cfg.C}, B={cfg.B}, {HP} head-problems",
+            "kmeans_ms": km, "kmeans_keys_per_s": HP * cfg.N / (km * 1e-3),
+            "roofline_assign": {"bound": "mfma", "achieved": tf, "peak": PEAK_BF16_MFMA_TFLOPS,
+                                "unit": "TFLOP/s", "frac": tf / PEAK_BF16_MFMA_TFLOPS,
+                                "flops_per_launch": flops, "launch_ms_avg": a_ms},
+            "decode_us_per_layer": d_ms * 1e3,
+            "recalled_kv_GBps": db["kv"] / (d_ms * 1e-3) / 1e9,
+            "decode_bytes_per_step": db["total"]}
 
 
 def incremental_decode():

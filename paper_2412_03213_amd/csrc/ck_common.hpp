@@ -32,33 +32,71 @@ __device__ __forceinline__ float hi_bf16(uint32_t w) {
 }
 
 // ---- cross-lane helpers ----
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, WAVE);
-  return v;
-}
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, WAVE));
-  return v;
-}
-__device__ __forceinline__ float wave_min(float v) {
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) v = fminf(v, __shfl_xor(v, m, WAVE));
-  return v;
-}
-// sum over the 16 lanes of a DPP row; every lane of the row gets the total
+// All built on DPP and the gfx950 lane-swap instructions (a few cycles each) instead
+// of ds_bpermute round trips through the LDS crossbar.  The butterflies combine the
+// same two partial results in every lane, so all lanes end with bit-identical values.
 template <int CTRL>
-__device__ __forceinline__ float dpp_row_ror(float v) {
-  return __builtin_bit_cast(
-      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
+__device__ __forceinline__ float dpp_f(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
 }
-__device__ __forceinline__ float row16_sum(float v) {
-  v += dpp_row_ror<0x128>(v);  // row_ror:8
-  v += dpp_row_ror<0x124>(v);  // row_ror:4
-  v += dpp_row_ror<0x122>(v);  // row_ror:2
-  v += dpp_row_ror<0x121>(v);  // row_ror:1
+template <int CTRL>
+__device__ __forceinline__ int dpp_i0(int v) {      // lanes without a source read 0
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true);
+}
+constexpr int DPP_XOR1 = 0xB1;          // quad_perm:[1,0,3,2]
+constexpr int DPP_XOR2 = 0x4E;          // quad_perm:[2,3,0,1]
+constexpr int DPP_HALF_MIRROR = 0x141;  // lane i <-> 7 - i inside each 8
+constexpr int DPP_MIRROR = 0x140;       // lane i <-> 15 - i inside each row of 16
+
+struct OpSum { __device__ __forceinline__ float operator()(float a, float b) const { return a + b; } };
+struct OpMax { __device__ __forceinline__ float operator()(float a, float b) const { return fmaxf(a, b); } };
+struct OpMin { __device__ __forceinline__ float operator()(float a, float b) const { return fminf(a, b); } };
+
+// v[i] (op) v[i ^ 16] and v[i] (op) v[i ^ 32]: v_permlane16_swap / v_permlane32_swap
+// applied to two copies of v leave "my half" in one result and "the other half" in the other.
+template <typename Op>
+__device__ __forceinline__ float xor16(float v, Op op) {
+  const unsigned u = __float_as_uint(v);
+  const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  return op(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+template <typename Op>
+__device__ __forceinline__ float xor32(float v, Op op) {
+  const unsigned u = __float_as_uint(v);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return op(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+// over the 16 lanes of a DPP row; every lane of the row gets the result
+template <typename Op>
+__device__ __forceinline__ float row16_reduce(float v, Op op) {
+  v = op(v, dpp_f<DPP_XOR1>(v));
+  v = op(v, dpp_f<DPP_XOR2>(v));
+  v = op(v, dpp_f<DPP_HALF_MIRROR>(v));
+  v = op(v, dpp_f<DPP_MIRROR>(v));
   return v;
+}
+template <typename Op>
+__device__ __forceinline__ float wave_reduce(float v, Op op) {
+  v = row16_reduce(v, op);
+  v = xor16(v, op);
+  return xor32(v, op);
+}
+__device__ __forceinline__ float row16_sum(float v) { return row16_reduce(v, OpSum()); }
+__device__ __forceinline__ float wave_sum(float v) { return wave_reduce(v, OpSum()); }
+__device__ __forceinline__ float wave_max(float v) { return wave_reduce(v, OpMax()); }
+__device__ __forceinline__ float wave_min(float v) { return wave_reduce(v, OpMin()); }
+
+// inclusive prefix sum over the 64 lanes
+__device__ __forceinline__ int wave_inclusive_scan(int v) {
+  v += dpp_i0<0x111>(v);   // row_shr:1
+  v += dpp_i0<0x112>(v);   // row_shr:2
+  v += dpp_i0<0x114>(v);   // row_shr:4
+  v += dpp_i0<0x118>(v);   // row_shr:8
+  const int t0 = __builtin_amdgcn_readlane(v, 15);
+  const int t1 = __builtin_amdgcn_readlane(v, 31);
+  const int t2 = __builtin_amdgcn_readlane(v, 47);
+  const int row = (threadIdx.x & 63) >> 4;
+  return v + (row >= 1 ? t0 : 0) + (row >= 2 ? t1 : 0) + (row >= 3 ? t2 : 0);
 }
 
 // Inclusive prefix sum over blockDim.x * ITEMS ints held ITEMS per thread in
@@ -69,18 +107,13 @@ __device__ __forceinline__ int block_inclusive_scan(int (&v)[ITEMS], int* tmp) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
 #pragma unroll
   for (int i = 1; i < ITEMS; ++i) v[i] += v[i - 1];
-  int run = v[ITEMS - 1];
-#pragma unroll
-  for (int o = 1; o < WAVE; o <<= 1) {
-    int t = __shfl_up(run, o, WAVE);
-    if (lane >= o) run += t;
-  }
+  const int run = wave_inclusive_scan(v[ITEMS - 1]);
   __syncthreads();  // tmp may still be in use by a previous call
   if (lane == WAVE - 1) tmp[wave] = run;
   __syncthreads();
   int wave_base = 0, total = 0;
   for (int w = 0; w < nwaves; ++w) {
-    int t = tmp[w];
+    const int t = tmp[w];
     if (w < wave) wave_base += t;
     total += t;
   }

@@ -35,19 +35,20 @@ constexpr int SELP_ITEMS = CK_MAX_CLUSTERS / SELP_THREADS;
 // LDS of one selection.  After select_prefix(): ord[j], cbeg[j], csz[j], cum[j] for
 // j < n_sel describe the recalled clusters in score order (cum = inclusive prefix
 // sum of their sizes).
-struct SelectLds {
+struct alignas(16) SelectLds {
   uint32_t key[CK_MAX_CLUSTERS];   // ~ordered(score): ascending key = descending score
   int ssz[CK_MAX_CLUSTERS];        // size per cluster id
   int soff[CK_MAX_CLUSTERS];       // offsets[cluster] per cluster id (when offsets are given)
   int ord[CK_MAX_CLUSTERS];        // cluster id per sorted position
   int cum[CK_MAX_CLUSTERS];        // inclusive prefix sum of sizes per sorted position
   int cbeg[SELP_MAX_CAND];         // offsets[cluster] per sorted position (candidate path only)
-  int cand[SELP_MAX_CAND];
+  int cand[SELP_MAX_CAND];         // candidate cluster ids (compacted, any order)
+  uint32_t ckey[SELP_MAX_CAND];    // their keys, dense, so that the ranking loop streams
   int bin_size[SELP_BINS];
   int bin_cnt[SELP_BINS];
   float red_f[2 * (SELP_THREADS / WAVE)];
   int tmp[SELP_THREADS / WAVE + 1];
-  int n_cand, n_sel, n_tok, counter, full_rank;
+  int n_cand, n_sel, n_tok, counter, full_rank, last_bin, n_app;
 };
 
 // Orders the clusters of one head-problem by descending score (ties: lower id
@@ -98,8 +99,12 @@ __device__ __forceinline__ void select_prefix(SelectLds& L, const float* __restr
     L.bin_size[b] = 0;
     L.bin_cnt[b] = 0;
   }
+  for (int i = tid; i < SELP_MAX_CAND; i += SELP_THREADS) {
+    L.ckey[i] = 0xFFFFFFFFu;                     // padding that never ranks before anything
+    L.cand[i] = 0x7FFFFFFF;
+  }
   if (tid == 0) {
-    L.n_cand = 0;
+    L.n_app = 0;
     L.counter = 0;
   }
   smax = wave_max(smax);
@@ -143,15 +148,7 @@ __device__ __forceinline__ void select_prefix(SelectLds& L, const float* __restr
       s[i] = ssum;
       n[i] = nsum;
     }
-    int sp = ssum, np = nsum;
-#pragma unroll
-    for (int o = 1; o < WAVE; o <<= 1) {
-      const int a = __shfl_up(sp, o, WAVE), b = __shfl_up(np, o, WAVE);
-      if (lane >= o) {
-        sp += a;
-        np += b;
-      }
-    }
+    const int sp = wave_inclusive_scan(ssum), np = wave_inclusive_scan(nsum);
     const int sbase = sp - ssum, nbase = np - nsum;
     int first = SELP_BINS, ncand = 0;
 #pragma unroll
@@ -162,45 +159,46 @@ __device__ __forceinline__ void select_prefix(SelectLds& L, const float* __restr
         ncand = nbase + n[i];
       }
     }
-    // lowest crossing bin over the wavefront
-    int best = first;
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) best = min(best, __shfl_xor(best, m, WAVE));
+    // lowest crossing bin over the wavefront (bin numbers are exact in fp32)
+    const int best = (int)wave_min((float)first);
     if (best == SELP_BINS) {                 // no crossing: every cluster is recalled
       if (lane == 0) {
-        L.counter = SELP_BINS - 1;
+        L.last_bin = SELP_BINS - 1;
         L.n_cand = C;
       }
     } else if (first == best) {
-      L.counter = best;
+      L.last_bin = best;
       L.n_cand = ncand;
     }
   }
   __syncthreads();
-  const int last_bin = L.counter, m = L.n_cand;
-  __syncthreads();
-  if (tid == 0) {
-    L.counter = 0;
-    L.n_cand = 0;
-  }
-  __syncthreads();
+  const int last_bin = L.last_bin, m = L.n_cand;
   if (m <= SELP_MAX_CAND) {
-    // ---- compact the candidates, then rank them among themselves ----
+    // ---- compact the candidates (id and key side by side), then rank them among
+    // themselves ----
 #pragma unroll
     for (int i = 0; i < SELP_ITEMS; ++i) {
       const int c = tid + i * SELP_THREADS;
-      if (c < C && bin[i] <= last_bin) L.cand[atomicAdd(&L.n_cand, 1)] = c;
+      if (c < C && bin[i] <= last_bin) {
+        const int pos = atomicAdd(&L.n_app, 1);
+        L.cand[pos] = c;
+        L.ckey[pos] = ~ordered_bits(sc[i]);
+      }
     }
     __syncthreads();
+    const int m_pad = (m + 3) & ~3;
     for (int i = tid; i < m; i += SELP_THREADS) {
       const int c = L.cand[i];
-      const uint32_t kc = L.key[c];
+      const uint32_t kc = L.ckey[i];
       const int ob = offsets ? L.soff[c] : 0;
       int rank = 0;
-      for (int j = 0; j < m; ++j) {
-        const int cj = L.cand[j];
-        const uint32_t kj = L.key[cj];
-        rank += (kj < kc || (kj == kc && cj < c)) ? 1 : 0;
+      for (int j = 0; j < m_pad; j += 4) {
+        const uint4 k4 = *reinterpret_cast<const uint4*>(&L.ckey[j]);
+        const int4 c4 = *reinterpret_cast<const int4*>(&L.cand[j]);
+        rank += (k4.x < kc || (k4.x == kc && c4.x < c)) ? 1 : 0;
+        rank += (k4.y < kc || (k4.y == kc && c4.y < c)) ? 1 : 0;
+        rank += (k4.z < kc || (k4.z == kc && c4.z < c)) ? 1 : 0;
+        rank += (k4.w < kc || (k4.w == kc && c4.w < c)) ? 1 : 0;
       }
       L.ord[rank] = c;
       L.cum[rank] = L.ssz[c];
@@ -227,6 +225,27 @@ __device__ __forceinline__ void select_prefix(SelectLds& L, const float* __restr
   }
   __syncthreads();
   // ---- inclusive prefix sum of the sizes in score order, and the recalled count ----
+  if (m <= WAVE) {
+    // the usual case (a few dozen candidates): one wavefront, no further barriers inside
+    if (wave == 0) {
+      const int own = lane < m ? L.cum[lane] : 0;
+      const int v = wave_inclusive_scan(own);
+      if (lane < m) L.cum[lane] = v;
+      const bool in = lane < m && (trim ? (v < budget) : (v <= budget));
+      int n_sel = __popcll(__ballot(in));
+      if (trim) n_sel = n_sel + 1 < m ? n_sel + 1 : m;
+      // prefix sum at position n_sel - 1, taken from the lane that holds it
+      int n_tok = n_sel > 0 ? __shfl(v, n_sel - 1, WAVE) : 0;
+      if (trim && n_tok > budget) n_tok = budget;
+      if (lane == 0) {
+        L.n_sel = n_sel;
+        L.n_tok = n_tok;
+        L.full_rank = 0;
+      }
+    }
+    __syncthreads();
+    return;
+  }
   int v[SELP_ITEMS];
 #pragma unroll
   for (int i = 0; i < SELP_ITEMS; ++i) {

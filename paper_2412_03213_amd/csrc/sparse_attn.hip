@@ -243,19 +243,11 @@ __global__ __launch_bounds__(ATT_THREADS) void k_attn_partial(const AttnArgs a) 
   if constexpr (FUSED) __syncthreads();   // red aliases arrays the row resolution read
 #pragma unroll
   for (int g = 0; g < G; ++g) {
-    float mx = fmaxf(m[g], __shfl_xor(m[g], 16, WAVE));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
+    const float mx = xor32(xor16(m[g], OpMax()), OpMax());
     const float w = __builtin_amdgcn_exp2f(m[g] - mx);
-    float ls = l[g] * w;
-    ls += __shfl_xor(ls, 16, WAVE);
-    ls += __shfl_xor(ls, 32, WAVE);
+    const float ls = xor32(xor16(l[g] * w, OpSum()), OpSum());
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      float v = acc[g][j] * w;
-      v += __shfl_xor(v, 16, WAVE);
-      v += __shfl_xor(v, 32, WAVE);
-      acc[g][j] = v;
-    }
+    for (int j = 0; j < 8; ++j) acc[g][j] = xor32(xor16(acc[g][j] * w, OpSum()), OpSum());
     if (lane < 16) {
       float* r = red + (wave * G + g) * PART_STRIDE;
       r[0] = mx;
