@@ -8,9 +8,11 @@ namespace ck {
 // largest byte stream of a decode step, so it is spread over many workgroups
 // (64 rows each) instead of one per head-problem; 16 lanes share a row.
 constexpr int SCORE_THREADS = 256;
-constexpr int SCORE_ROWS = 64;
 
-template <typename T>
+// SCORE_ROWS centroid rows per workgroup: 64 when there are few head-problems (more
+// workgroups, lower latency), 256 when there are many (more bytes in flight per
+// workgroup, fewer workgroups to dispatch).
+template <typename T, int SCORE_ROWS>
 __global__ __launch_bounds__(SCORE_THREADS) void k_score(
     const T* __restrict__ q, const T* __restrict__ centroids, int Hq, int Hkv, int G, int C_cap,
     int n_clusters, float* __restrict__ scores) {
@@ -48,13 +50,18 @@ __global__ __launch_bounds__(SCORE_THREADS) void k_score(
 
 hipError_t launch_score(const Dims& dm, const void* q, const void* centroids, int n_clusters,
                         float* scores, hipStream_t st) {
-  const dim3 grid((n_clusters + SCORE_ROWS - 1) / SCORE_ROWS, dm.HP);
-  if (dm.dtype == CK_BF16)
-    hipLaunchKernelGGL(k_score<bf16>, grid, dim3(SCORE_THREADS), 0, st, (const bf16*)q,
-                       (const bf16*)centroids, dm.Hq, dm.Hkv, dm.G, dm.C_cap, n_clusters, scores);
-  else
-    hipLaunchKernelGGL(k_score<float>, grid, dim3(SCORE_THREADS), 0, st, (const float*)q,
-                       (const float*)centroids, dm.Hq, dm.Hkv, dm.G, dm.C_cap, n_clusters, scores);
+  const bool many = (int64_t)dm.HP * ((n_clusters + 63) / 64) > 2048;
+  const int rows = many ? 256 : 64;
+  const dim3 grid((n_clusters + rows - 1) / rows, dm.HP);
+#define CK_SCORE(TT, RR)                                                                    \
+  hipLaunchKernelGGL((k_score<TT, RR>), grid, dim3(SCORE_THREADS), 0, st, (const TT*)q,     \
+                     (const TT*)centroids, dm.Hq, dm.Hkv, dm.G, dm.C_cap, n_clusters, scores)
+  if (dm.dtype == CK_BF16) {
+    if (many) CK_SCORE(bf16, 256); else CK_SCORE(bf16, 64);
+  } else {
+    if (many) CK_SCORE(float, 256); else CK_SCORE(float, 64);
+  }
+#undef CK_SCORE
   return hipGetLastError();
 }
 
