@@ -3,13 +3,16 @@
 // with the cluster selection and index generation of Sections III-C / IV-C.
 //
 // HBM-bound: every recalled K and V row (256 B in bf16) is read exactly once per
-// KV head and shared by the G query heads of the group.  A 16-lane group owns one
-// token at a time (16 B of the row per lane, so a wavefront load instruction
-// covers four whole rows = eight 128-byte lines); the attended positions of a
-// head-problem are split over several workgroups (split-KV) so that a batch of a
-// few sequences still fills 256 CUs, and a small second kernel merges the
-// partial (max, sum, accumulator) triples.  Inside a workgroup the token rows of
-// its positions are resolved into LDS first, so the K/V loads of the next step
+// KV head and shared by the G query heads of the group.  A wavefront takes 16
+// tokens per step.  V rows are owned by 16-lane groups (16 B of the row per lane)
+// and accumulated on the vector ALUs; in bf16 the K rows go straight into
+// v_mfma_f32_16x16x32_bf16 as the A operand with the query heads as B columns,
+// which removes the unpacking, the dot products and their cross-lane reductions
+// from the vector ALUs (fp32 check mode keeps the all-VALU form).  The attended
+// positions of a head-problem are split over several workgroups (split-KV) so that
+// a batch of a few sequences still fills 256 CUs, and a small second kernel merges
+// the partial (max, sum, accumulator) triples.  Inside a workgroup the token rows
+// of its positions are resolved into LDS first, so the K/V loads of the next step
 // are always in flight while the current one is reduced.
 //
 // Fused mode: every workgroup of a head-problem repeats the (cheap, LDS-only)
@@ -28,6 +31,7 @@ constexpr int ATT_STEP_TOKENS = 16 * ATT_UNROLL;   // 64 tokens per workgroup it
 constexpr int ATT_MAX_CHUNK = 4096;        // positions one workgroup may own (rows held in LDS)
 constexpr float NEG_BIG = -1.0e30f;        // "no token yet": finite so that differences stay finite
 constexpr int ATT_TARGET_WGS = 512;        // 2 per CU on 256 CUs
+constexpr int PEX_WAVE = 16 * 8 + 8;             // floats of probability exchange per wavefront (G <= 8)
 constexpr int PART_STRIDE = D + 2;         // floats per (split, query head): max, sum, acc[128]
 
 template <typename T> struct RawRow;
@@ -85,21 +89,13 @@ template <typename T, int G, bool FUSED>
 __global__ __launch_bounds__(ATT_THREADS) void k_attn_partial(const AttnArgs a) {
   using Lds = typename std::conditional<FUSED, SelectLds, AttnPlainLds<G>>::type;
   __shared__ Lds lds;
+  __shared__ __attribute__((aligned(16))) float pex[4 * PEX_WAVE];
   int* rows;
   float* red;
   const int split = blockIdx.x, hp = blockIdx.y, tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6, l16 = tid & 15, slot = tid >> 4;  // 16 slots
   const int s = hp / a.Hkv, h = hp % a.Hkv;
   const T* q = static_cast<const T*>(a.q);
-
-  // this lane's 8 channels of every query head of the group, pre-scaled
-  float qv[G][8];
-#pragma unroll
-  for (int g = 0; g < G; ++g) {
-    load_row8<T>(q + ((int64_t)s * a.Hq + h * G + g) * D + l16 * 8, qv[g]);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) qv[g][j] *= a.scale_log2e;
-  }
 
   int n_idx;
   if constexpr (FUSED) {
@@ -167,93 +163,229 @@ __global__ __launch_bounds__(ATT_THREADS) void k_attn_partial(const AttnArgs a) 
   }
   __syncthreads();
 
-  float m[G], l[G], acc[G][8];
+  float acc[G][8];
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    m[g] = NEG_BIG;
-    l[g] = 0.f;
+  for (int g = 0; g < G; ++g)
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[g][j] = 0.f;
-  }
-
-  const T* Khp = static_cast<const T*>(a.K) + (int64_t)hp * a.N_cap * D + l16 * 8;
   const T* Vhp = static_cast<const T*>(a.V) + (int64_t)hp * a.N_cap * D + l16 * 8;
-  RawRow<T> kc[ATT_UNROLL], vc[ATT_UNROLL], kn[ATT_UNROLL], vn[ATT_UNROLL];
-  auto fetch = [&](int i0, RawRow<T>(&kr)[ATT_UNROLL], RawRow<T>(&vr)[ATT_UNROLL]) {
+
+  if constexpr (std::is_same<T, bf16>::value) {
+    // ---- bf16: q K^T on the matrix cores ----
+    // One v_mfma_f32_16x16x32_bf16 per 32-channel slab: A = 16 token rows of the
+    // step (lane: token lane%16, channels 8*(lane/16)..+8 of the slab), B = the
+    // query heads as columns (column >= G is zero).  The result leaves lane
+    // (g + 16u) with the scores of tokens (u, 0..3) for head g, so the running
+    // max / sum of a head live in the four lanes of its column and the
+    // probabilities reach the lanes that own the V rows through a few hundred
+    // bytes of wavefront-private LDS.  All four token slots of a wavefront share
+    // one running max per head.
+    const int col = lane & 15, kg = lane >> 4;          // kg is also this lane's slot in the wavefront
+    bf16x8 qb[4];
 #pragma unroll
-    for (int u = 0; u < ATT_UNROLL; ++u) {
-      const int i = i0 + u * 16 + slot;
-      const int64_t row = i < n_pos ? rows[i] : 0;
-      kr[u].load(Khp + row * D);
-      vr[u].load(Vhp + row * D);
+    for (int sl = 0; sl < 4; ++sl) {
+      uint4 w = make_uint4(0, 0, 0, 0);
+      if (col < G)
+        w = *reinterpret_cast<const uint4*>(q + ((int64_t)s * a.Hq + h * G + col) * D + sl * 32 + kg * 8);
+      qb[sl] = __builtin_bit_cast(bf16x8, w);
     }
-  };
-  if (n_pos > 0) fetch(0, kc, vc);
-  for (int i0 = 0; i0 < n_pos; i0 += ATT_STEP_TOKENS) {
-    if (i0 + ATT_STEP_TOKENS < n_pos) fetch(i0 + ATT_STEP_TOKENS, kn, vn);
-    float kv[ATT_UNROLL][8];
+    float m_run = NEG_BIG, l_run = 0.f;                 // of head `col`, identical in its four lanes
+    float* px = pex + wave * PEX_WAVE;                  // [slot][u][g] probabilities, then [g] rescale factors
+    const bf16* Khp = static_cast<const bf16*>(a.K) + (int64_t)hp * a.N_cap * D + kg * 8;
+    const int tpos = (col >> 2) * 16 + wave * 4 + (col & 3);   // A row `col` = token (u = col/4, slot = col%4)
+    uint4 kc[4], kn[4], vc[ATT_UNROLL], vn[ATT_UNROLL];
+    auto fetch = [&](int i0, uint4(&kr)[4], uint4(&vr)[ATT_UNROLL]) {
+      const int ik = i0 + tpos;
+      const bf16* kp = Khp + (int64_t)(ik < n_pos ? rows[ik] : 0) * D;
 #pragma unroll
-    for (int u = 0; u < ATT_UNROLL; ++u) kc[u].unpack(kv[u]);
-    float sc[G][ATT_UNROLL];
-#pragma unroll
-    for (int g = 0; g < G; ++g)
+      for (int sl = 0; sl < 4; ++sl) kr[sl] = *reinterpret_cast<const uint4*>(kp + sl * 32);
 #pragma unroll
       for (int u = 0; u < ATT_UNROLL; ++u) {
-        float d = 0.f;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) d = fmaf(qv[g][j], kv[u][j], d);
-        d = row16_sum(d);
-        sc[g][u] = (i0 + u * 16 + slot < n_pos) ? d : -INFINITY;
+        const int i = i0 + u * 16 + slot;
+        vr[u] = *reinterpret_cast<const uint4*>(Vhp + (int64_t)(i < n_pos ? rows[i] : 0) * D);
       }
-    float pw[G][ATT_UNROLL];
+    };
+    if (n_pos > 0) fetch(0, kc, vc);
+    for (int i0 = 0; i0 < n_pos; i0 += ATT_STEP_TOKENS) {
+      if (i0 + ATT_STEP_TOKENS < n_pos) fetch(i0 + ATT_STEP_TOKENS, kn, vn);
+      floatx4 d = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-      float mx = m[g];
+      for (int sl = 0; sl < 4; ++sl)
+        d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kc[sl]), qb[sl], d, 0, 0, 0);
+      // d[i]: token (u = kg, slot i) against head `col`
+      float sc[4];
+      const int ibase = i0 + kg * 16 + wave * 4;
 #pragma unroll
-      for (int u = 0; u < ATT_UNROLL; ++u) mx = fmaxf(mx, sc[g][u]);
-      const float corr = __builtin_amdgcn_exp2f(m[g] - mx);
-      m[g] = mx;
-      float ls = l[g] * corr;
+      for (int i = 0; i < 4; ++i) sc[i] = (ibase + i < n_pos) ? d[i] * a.scale_log2e : -INFINITY;
+      float mx = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
+      mx = xor32(xor16(mx, OpMax()), OpMax());
+      mx = fmaxf(mx, m_run);
+      const float corr = __builtin_amdgcn_exp2f(m_run - mx);
+      m_run = mx;
+      float pw[4];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) acc[g][j] *= corr;
+      for (int i = 0; i < 4; ++i) pw[i] = __builtin_amdgcn_exp2f(sc[i] - mx);
+      float ps = (pw[0] + pw[1]) + (pw[2] + pw[3]);
+      ps = xor32(xor16(ps, OpSum()), OpSum());
+      l_run = l_run * corr + ps;
+      if (col < G) {
 #pragma unroll
-      for (int u = 0; u < ATT_UNROLL; ++u) {
-        pw[g][u] = __builtin_amdgcn_exp2f(sc[g][u] - mx);
-        ls += pw[g][u];
+        for (int i = 0; i < 4; ++i) px[(i * 4 + kg) * G + col] = pw[i];
+        if (kg == 0) px[16 * G + col] = corr;
       }
-      l[g] = ls;
-    }
+      // LDS serves one wavefront's requests in order: the reads below see the writes above
+      __builtin_amdgcn_wave_barrier();
+      asm volatile("" ::: "memory");
+      float pr[ATT_UNROLL][G], cr[G];
+      {
+        const floatx4* src = reinterpret_cast<const floatx4*>(px + kg * 4 * G);
+        floatx4 tmp[G];
 #pragma unroll
-    for (int u = 0; u < ATT_UNROLL; ++u) {
-      float vv[8];
-      vc[u].unpack(vv);
+        for (int k = 0; k < G; ++k) tmp[k] = src[k];
+#pragma unroll
+        for (int k = 0; k < G; ++k)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) pr[(k * 4 + e) / G][(k * 4 + e) % G] = tmp[k][e];
+#pragma unroll
+        for (int g = 0; g < G; ++g) cr[g] = px[16 * G + g];
+      }
+      asm volatile("" ::: "memory");
+      __builtin_amdgcn_wave_barrier();
 #pragma unroll
       for (int g = 0; g < G; ++g)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc[g][j] = fmaf(pw[g][u], vv[j], acc[g][j]);
+        for (int j = 0; j < 8; ++j) acc[g][j] *= cr[g];
+#pragma unroll
+      for (int u = 0; u < ATT_UNROLL; ++u) {
+        float vv[8];
+        vv[0] = lo_bf16(vc[u].x); vv[1] = hi_bf16(vc[u].x); vv[2] = lo_bf16(vc[u].y); vv[3] = hi_bf16(vc[u].y);
+        vv[4] = lo_bf16(vc[u].z); vv[5] = hi_bf16(vc[u].z); vv[6] = lo_bf16(vc[u].w); vv[7] = hi_bf16(vc[u].w);
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+          for (int j = 0; j < 8; ++j) acc[g][j] = fmaf(pr[u][g], vv[j], acc[g][j]);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        kc[u] = kn[u];
+        vc[u] = vn[u];
+      }
     }
+    // ---- combine the 4 slots of a wavefront: they share the running max ----
+    if constexpr (FUSED) __syncthreads();   // red aliases arrays the row resolution read
 #pragma unroll
-    for (int u = 0; u < ATT_UNROLL; ++u) {
-      kc[u] = kn[u];
-      vc[u] = vn[u];
-    }
-  }
-
-  // ---- combine the 4 slots of a wavefront (lanes l16 + 16*k) ----
-  if constexpr (FUSED) __syncthreads();   // red aliases arrays the row resolution read
+    for (int g = 0; g < G; ++g)
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    const float mx = xor32(xor16(m[g], OpMax()), OpMax());
-    const float w = __builtin_amdgcn_exp2f(m[g] - mx);
-    const float ls = xor32(xor16(l[g] * w, OpSum()), OpSum());
-#pragma unroll
-    for (int j = 0; j < 8; ++j) acc[g][j] = xor32(xor16(acc[g][j] * w, OpSum()), OpSum());
+      for (int j = 0; j < 8; ++j) acc[g][j] = xor32(xor16(acc[g][j], OpSum()), OpSum());
     if (lane < 16) {
-      float* r = red + (wave * G + g) * PART_STRIDE;
-      r[0] = mx;
-      r[1] = ls;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) r[2 + l16 * 8 + j] = acc[g][j];
+      for (int g = 0; g < G; ++g) {
+        float* r = red + (wave * G + g) * PART_STRIDE;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) r[2 + l16 * 8 + j] = acc[g][j];
+      }
+      if (lane < G) {
+        float* r = red + (wave * G + lane) * PART_STRIDE;
+        r[0] = m_run;
+        r[1] = l_run;
+      }
+    }
+  } else {
+    // ---- fp32 check mode: dot products on the vector ALUs ----
+    // this lane's 8 channels of every query head of the group, pre-scaled
+    float qv[G][8];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      load_row8<T>(q + ((int64_t)s * a.Hq + h * G + g) * D + l16 * 8, qv[g]);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) qv[g][j] *= a.scale_log2e;
+    }
+
+    float m[G], l[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      m[g] = NEG_BIG;
+      l[g] = 0.f;
+    }
+
+    const T* Khp = static_cast<const T*>(a.K) + (int64_t)hp * a.N_cap * D + l16 * 8;
+    RawRow<T> kc[ATT_UNROLL], vc[ATT_UNROLL], kn[ATT_UNROLL], vn[ATT_UNROLL];
+    auto fetch = [&](int i0, RawRow<T>(&kr)[ATT_UNROLL], RawRow<T>(&vr)[ATT_UNROLL]) {
+#pragma unroll
+      for (int u = 0; u < ATT_UNROLL; ++u) {
+        const int i = i0 + u * 16 + slot;
+        const int64_t row = i < n_pos ? rows[i] : 0;
+        kr[u].load(Khp + row * D);
+        vr[u].load(Vhp + row * D);
+      }
+    };
+    if (n_pos > 0) fetch(0, kc, vc);
+    for (int i0 = 0; i0 < n_pos; i0 += ATT_STEP_TOKENS) {
+      if (i0 + ATT_STEP_TOKENS < n_pos) fetch(i0 + ATT_STEP_TOKENS, kn, vn);
+      float kv[ATT_UNROLL][8];
+#pragma unroll
+      for (int u = 0; u < ATT_UNROLL; ++u) kc[u].unpack(kv[u]);
+      float sc[G][ATT_UNROLL];
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int u = 0; u < ATT_UNROLL; ++u) {
+          float d = 0.f;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) d = fmaf(qv[g][j], kv[u][j], d);
+          d = row16_sum(d);
+          sc[g][u] = (i0 + u * 16 + slot < n_pos) ? d : -INFINITY;
+        }
+      float pw[G][ATT_UNROLL];
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        float mx = m[g];
+#pragma unroll
+        for (int u = 0; u < ATT_UNROLL; ++u) mx = fmaxf(mx, sc[g][u]);
+        const float corr = __builtin_amdgcn_exp2f(m[g] - mx);
+        m[g] = mx;
+        float ls = l[g] * corr;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[g][j] *= corr;
+#pragma unroll
+        for (int u = 0; u < ATT_UNROLL; ++u) {
+          pw[g][u] = __builtin_amdgcn_exp2f(sc[g][u] - mx);
+          ls += pw[g][u];
+        }
+        l[g] = ls;
+      }
+#pragma unroll
+      for (int u = 0; u < ATT_UNROLL; ++u) {
+        float vv[8];
+        vc[u].unpack(vv);
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+          for (int j = 0; j < 8; ++j) acc[g][j] = fmaf(pw[g][u], vv[j], acc[g][j]);
+      }
+#pragma unroll
+      for (int u = 0; u < ATT_UNROLL; ++u) {
+        kc[u] = kn[u];
+        vc[u] = vn[u];
+      }
+    }
+
+    // ---- combine the 4 slots of a wavefront (lanes l16 + 16*k) ----
+    if constexpr (FUSED) __syncthreads();   // red aliases arrays the row resolution read
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const float mx = xor32(xor16(m[g], OpMax()), OpMax());
+      const float w = __builtin_amdgcn_exp2f(m[g] - mx);
+      const float ls = xor32(xor16(l[g] * w, OpSum()), OpSum());
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[g][j] = xor32(xor16(acc[g][j] * w, OpSum()), OpSum());
+      if (lane < 16) {
+        float* r = red + (wave * G + g) * PART_STRIDE;
+        r[0] = mx;
+        r[1] = ls;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) r[2 + l16 * 8 + j] = acc[g][j];
+      }
     }
   }
   __syncthreads();
