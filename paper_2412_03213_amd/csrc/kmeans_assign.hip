@@ -11,20 +11,26 @@
 // (max, argmax) lives in plain registers and only one exchange between lanes
 // l and l+32 is needed at the very end.  Keys stay in registers for the whole
 // kernel (NKB blocks of 32 keys per wavefront); centroid tiles stream through
-// LDS in double-buffered chunks of 64 rows shared by the four wavefronts.
+// LDS in double-buffered chunks of 64 rows shared by all wavefronts of the workgroup.
 #include "ck_common.hpp"
 
 namespace ck {
 
 constexpr int CHUNK_ROWS = 64;             // centroid rows per LDS chunk (two MFMA tiles)
 constexpr int LDS_ROW = D + 8;             // bf16 elements per LDS row: 272 B, rows shift 4 banks
-constexpr int ASSIGN_THREADS = 256;
 
-template <int NKB, int WAVES_PER_SIMD>
-__global__ __launch_bounds__(ASSIGN_THREADS, WAVES_PER_SIMD) void k_assign(
+// WAVES wavefronts per workgroup, each with NKB blocks of 32 keys.  With PHASED the
+// odd wavefronts of a SIMD pair (waves >= WAVES/2 share SIMDs with waves < WAVES/2)
+// delay the accumulator read-out of a tile until after the next barrier, so that on
+// every SIMD one wavefront is in its MFMA phase while the other reduces on the
+// vector ALUs.
+template <int NKB, int WAVES, int WAVES_PER_SIMD, bool PHASED>
+__global__ __launch_bounds__(WAVES * 64, WAVES_PER_SIMD) void k_assign(
     const bf16* __restrict__ K, const bf16* __restrict__ mu_hat, int32_t* __restrict__ labels,
-    float* __restrict__ best_sim, int32_t* __restrict__ chunk_hist, int64_t N_cap,
-    int64_t tok_begin, int64_t tok_count, int c_begin, int c_count) {
+    float* __restrict__ best_sim, int32_t* __restrict__ chunk_hist, int n_hist_chunks,
+    int64_t N_cap, int64_t tok_begin, int64_t tok_count, int c_begin, int c_count) {
+  constexpr int THREADS = WAVES * 64;
+  constexpr int SEGS = CHUNK_ROWS * 16 / THREADS;      // 16-byte segments of a chunk per thread
   __shared__ __attribute__((aligned(16))) bf16 lds[2][CHUNK_ROWS * LDS_ROW];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -34,12 +40,12 @@ __global__ __launch_bounds__(ASSIGN_THREADS, WAVES_PER_SIMD) void k_assign(
   const bf16* Mhp = mu_hat + (int64_t)hp * c_count * D;
 
   const int n_chunks = (c_count + CHUNK_ROWS - 1) / CHUNK_ROWS;
-  uint4 stage[4];
-  // chunk = 64 rows x 256 B = 1024 segments of 16 B; thread handles 4 of them
+  const int n_tiles = (c_count + 31) / 32;
+  uint4 stage[SEGS];
   auto fetch = [&](int ch) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int seg = tid + i * ASSIGN_THREADS;
+    for (int i = 0; i < SEGS; ++i) {
+      const int seg = tid + i * THREADS;
       const int r = ch * CHUNK_ROWS + (seg >> 4);
       if (r < c_count)
         stage[i] = *reinterpret_cast<const uint4*>(Mhp + (int64_t)r * D + (seg & 15) * 8);
@@ -49,8 +55,8 @@ __global__ __launch_bounds__(ASSIGN_THREADS, WAVES_PER_SIMD) void k_assign(
   };
   auto stash = [&](int buf) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int seg = tid + i * ASSIGN_THREADS;
+    for (int i = 0; i < SEGS; ++i) {
+      const int seg = tid + i * THREADS;
       *reinterpret_cast<uint4*>(&lds[buf][(seg >> 4) * LDS_ROW + (seg & 15) * 8]) = stage[i];
     }
   };
@@ -61,7 +67,7 @@ __global__ __launch_bounds__(ASSIGN_THREADS, WAVES_PER_SIMD) void k_assign(
   // Issued fragment-major (all key blocks' fragment 0, then fragment 1, ...): the first
   // tile's MFMAs then start as soon as the first few loads have landed and follow the
   // arriving data instead of waiting for all of it.
-  const int64_t wave_tok0 = ((int64_t)blockIdx.x * 4 + wave) * (NKB * 32);
+  const int64_t wave_tok0 = ((int64_t)blockIdx.x * WAVES + wave) * (NKB * 32);
   bf16x8 bk[NKB][8];
   {
     const bf16* rows[NKB];
@@ -90,65 +96,89 @@ __global__ __launch_bounds__(ASSIGN_THREADS, WAVES_PER_SIMD) void k_assign(
     bestp[kb] = -INFINITY;
     btile[kb] = 0;
   }
+  floatx16 acc[NKB];
+
+  // similarities of centroid tile `t` (rows of chunk buffer `buf`) against the keys
+  auto contract = [&](const bf16* buf, int tile) {
+#pragma unroll
+    for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[kb][i] = 0.f;
+    const bf16* arow = buf + (tile * 32 + col) * LDS_ROW + half * 8;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(arow + kk * 16);
+#pragma unroll
+      for (int kb = 0; kb < NKB; ++kb)
+        acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bk[kb][kk], acc[kb], 0, 0, 0);
+    }
+  };
+  // folds the accumulators of tile `tile_id` into the running maxima
+  auto reduce = [&](int tile_id) {
+    const int row0 = tile_id * 32;
+    // accumulator i of a lane is centroid row 8*(i/4) + 4*half + i%4 of the tile
+    if (row0 + 32 > c_count) {                         // wave-uniform: zero-padded rows lose
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int c = row0 + 8 * (i >> 2) + 4 * half + (i & 3);
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb)
+          if (c >= c_count) acc[kb][i] = -3.0e38f;     // finite: the slot bits must not make a NaN
+      }
+    }
+#pragma unroll
+    for (int kb = 0; kb < NKB; ++kb) {
+      float p[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        p[i] = __uint_as_float((__float_as_uint(acc[kb][i]) & 0xFFFFFFF0u) | (uint32_t)(15 - i));
+      float m = bestp[kb];
+      m = fmaxf(fmaxf(m, p[0]), p[1]);
+#pragma unroll
+      for (int i = 2; i < 16; i += 2) m = fmaxf(fmaxf(m, p[i]), p[i + 1]);
+      btile[kb] = (m != bestp[kb]) ? tile_id : btile[kb];
+      bestp[kb] = m;
+    }
+  };
 
   stash(0);
   __syncthreads();
 
+  const bool late = PHASED && wave >= WAVES / 2;        // wave-uniform
   for (int ch = 0; ch < n_chunks; ++ch) {
     if (ch + 1 < n_chunks) fetch(ch + 1);
     const bf16* buf = lds[ch & 1];
+    if (!late) {
 #pragma unroll
-    for (int tile = 0; tile < 2; ++tile) {
-      const int row0 = ch * CHUNK_ROWS + tile * 32;
-      if (row0 < c_count) {                            // wave-uniform
-        floatx16 acc[NKB];
-#pragma unroll
-        for (int kb = 0; kb < NKB; ++kb)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) acc[kb][i] = 0.f;
-        const bf16* arow = buf + (tile * 32 + col) * LDS_ROW + half * 8;
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-          const bf16x8 a = *reinterpret_cast<const bf16x8*>(arow + kk * 16);
-#pragma unroll
-          for (int kb = 0; kb < NKB; ++kb)
-            acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bk[kb][kk], acc[kb], 0, 0, 0);
+      for (int tile = 0; tile < 2; ++tile) {
+        const int t = ch * 2 + tile;
+        if (t < n_tiles) {                               // wave-uniform
+          contract(buf, tile);
+          reduce(t);
         }
-        // accumulator i of a lane is centroid row 8*(i/4) + 4*half + i%4 of the tile
-        if (row0 + 32 > c_count) {                     // wave-uniform: zero-padded rows lose
+      }
+    } else {
 #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const int c = row0 + 8 * (i >> 2) + 4 * half + (i & 3);
-#pragma unroll
-            for (int kb = 0; kb < NKB; ++kb)
-              if (c >= c_count) acc[kb][i] = -3.0e38f;   // finite: the slot bits must not make a NaN
-          }
-        }
-        const int tile_id = ch * 2 + tile;
-#pragma unroll
-        for (int kb = 0; kb < NKB; ++kb) {
-          float p[16];
-#pragma unroll
-          for (int i = 0; i < 16; ++i)
-            p[i] = __uint_as_float((__float_as_uint(acc[kb][i]) & 0xFFFFFFF0u) | (uint32_t)(15 - i));
-          float m = bestp[kb];
-          m = fmaxf(fmaxf(m, p[0]), p[1]);
-#pragma unroll
-          for (int i = 2; i < 16; i += 2) m = fmaxf(fmaxf(m, p[i]), p[i + 1]);
-          btile[kb] = (m != bestp[kb]) ? tile_id : btile[kb];
-          bestp[kb] = m;
+      for (int tile = 0; tile < 2; ++tile) {
+        const int t = ch * 2 + tile;
+        if (t < n_tiles) {
+          if (t > 0) reduce(t - 1);
+          contract(buf, tile);
         }
       }
     }
     if (ch + 1 < n_chunks) stash((ch + 1) & 1);
     __syncthreads();
   }
+  if (late) reduce(n_tiles - 1);
 
   // ---- lanes l and l+32 hold the two halves of each key's candidates ----
   // (the centroid buffers are free now: the loop ended with a barrier)
-  int* hist = reinterpret_cast<int*>(&lds[0][0]);
+  // One label histogram per 4 wavefronts = per chunk of the counting sort.
+  constexpr int HISTS = WAVES / 4;
+  int* hist = reinterpret_cast<int*>(&lds[0][0]) + (wave >> 2) * c_count;
   if (chunk_hist) {
-    for (int c = tid; c < c_count; c += ASSIGN_THREADS) hist[c] = 0;
+    for (int c = tid; c < HISTS * c_count; c += THREADS) reinterpret_cast<int*>(&lds[0][0])[c] = 0;
     __syncthreads();
   }
 #pragma unroll
@@ -173,29 +203,37 @@ __global__ __launch_bounds__(ASSIGN_THREADS, WAVES_PER_SIMD) void k_assign(
       if (chunk_hist) atomicAdd(&hist[bidx], 1);       // integer counts: order does not matter
     }
   }
-  // label histogram of this workgroup's tokens = one chunk of the counting sort
+  // label histograms of this workgroup's tokens = chunks of the counting sort
   if (chunk_hist) {
     __syncthreads();
-    int32_t* out = chunk_hist + ((int64_t)hp * gridDim.x + blockIdx.x) * c_count;
-    for (int c = tid; c < c_count; c += ASSIGN_THREADS) out[c] = hist[c];
+    for (int e = tid; e < HISTS * c_count; e += THREADS) {
+      const int hc = (int)blockIdx.x * HISTS + e / c_count;
+      if (hc < n_hist_chunks)
+        chunk_hist[((int64_t)hp * n_hist_chunks + hc) * c_count + e % c_count] =
+            reinterpret_cast<int*>(&lds[0][0])[e];
+    }
   }
 }
 
-template <int NKB, int WPS>
+template <int NKB, int WAVES, int WPS, bool PHASED>
 static void launch_assign_variant(const Dims& dm, const bf16* K, int64_t tok_begin,
                                   int64_t tok_count, const bf16* mu_hat, int c_begin, int c_count,
                                   int32_t* labels, float* best_sim, int32_t* chunk_hist,
                                   hipStream_t st) {
-  dim3 grid((unsigned)((tok_count + 4 * NKB * 32 - 1) / (4 * NKB * 32)), dm.HP);
-  hipLaunchKernelGGL((k_assign<NKB, WPS>), grid, dim3(ASSIGN_THREADS), 0, st, K, mu_hat, labels,
-                     best_sim, chunk_hist, dm.N_cap, tok_begin, tok_count, c_begin, c_count);
+  constexpr int TOK = WAVES * NKB * 32;
+  const int sort_chunk = 4 * NKB * 32;
+  const int n_hist_chunks = (int)((tok_count + sort_chunk - 1) / sort_chunk);
+  dim3 grid((unsigned)((tok_count + TOK - 1) / TOK), dm.HP);
+  hipLaunchKernelGGL((k_assign<NKB, WAVES, WPS, PHASED>), grid, dim3(WAVES * 64), 0, st, K, mu_hat,
+                     labels, best_sim, chunk_hist, n_hist_chunks, dm.N_cap, tok_begin, tok_count,
+                     c_begin, c_count);
 }
 
-// Tokens one assignment workgroup labels; also the chunk size of the counting sort
-// (the workgroup emits the label histogram of exactly its own tokens).
-// Large problems: 128 keys per wavefront (4 MFMAs per centroid fragment read).
-// Small ones (incremental clustering of a few hundred tokens): 32 keys per
-// wavefront so that more workgroups exist.
+// Chunk size of the counting sort = the tokens of four assignment wavefronts (every
+// group of four emits the label histogram of exactly its own tokens).
+// Large problems: 128 keys per wavefront (4 MFMAs per centroid fragment read), eight
+// wavefronts per workgroup.  Small ones (incremental clustering of a few hundred
+// tokens): 32 keys per wavefront, four per workgroup, so that more workgroups exist.
 int assign_tile_tokens(const Dims& dm, int64_t tok_count) {
   return tok_count * dm.HP >= 64 * 1024 ? 512 : 128;
 }
@@ -204,11 +242,11 @@ hipError_t launch_assign(const Dims& dm, const bf16* K, int64_t tok_begin, int64
                          const bf16* mu_hat, int c_begin, int c_count, int32_t* labels,
                          float* best_sim, int32_t* chunk_hist, hipStream_t st) {
   if (assign_tile_tokens(dm, tok_count) == 512)
-    launch_assign_variant<4, 2>(dm, K, tok_begin, tok_count, mu_hat, c_begin, c_count, labels,
-                                best_sim, chunk_hist, st);
+    launch_assign_variant<4, 8, 2, true>(dm, K, tok_begin, tok_count, mu_hat, c_begin, c_count,
+                                         labels, best_sim, chunk_hist, st);
   else
-    launch_assign_variant<1, 4>(dm, K, tok_begin, tok_count, mu_hat, c_begin, c_count, labels,
-                                best_sim, chunk_hist, st);
+    launch_assign_variant<1, 4, 4, false>(dm, K, tok_begin, tok_count, mu_hat, c_begin, c_count,
+                                          labels, best_sim, chunk_hist, st);
   return hipGetLastError();
 }
 
