@@ -20,7 +20,8 @@ Readings taken where the paper is silent (each is listed in the design notes):
     rounded to the storage type of the centroid table;
   * an empty cluster keeps its previous centroid and stays in the table;
   * ties (equal similarity, equal score) go to the lower cluster id;
-  * a fixed iteration count replaces the run-to-convergence loop;
+  * a fixed iteration count replaces the run-to-convergence loop by default;
+    `kmeans_run` can also stop at the first assignment that changes no label;
   * cluster score = sum over the G query heads of <q_g, centroid>, no 1/sqrt(d);
   * budget: WHOLE keeps the longest prefix of the score order whose sizes sum to
     at most B; TRIM_LAST (the paper's rule) extends the prefix until the sum
@@ -29,7 +30,9 @@ Readings taken where the paper is silent (each is listed in the design notes):
 Pin status: every function below is pinned by tests/test_oracle_*.py (worked
 example of Fig. 8, closed forms, invariants, library cross-checks, loop-only
 brute force).  The 10-iteration K-means trajectory as a whole has no printed
-values to compare with: "parity unpinned" for `kmeans` beyond its per-step pins.
+values to compare with: "parity unpinned" for `kmeans` and `kmeans_run` beyond
+their per-step pins (the l2 variant is pinned as a whole against a library
+Lloyd iteration on data without near-ties).
 """
 from __future__ import annotations
 
@@ -166,6 +169,91 @@ def kmeans(keys, init_idx, n_iter, storage="bf16"):
 
 
 # --------------------------------------------------------------------------
+# K-means variants: other distance metrics (the ablation of Section V-B) and
+# the run-until-convergence loop of Section III-B
+# --------------------------------------------------------------------------
+COSINE = "cosine"
+L2 = "l2"
+INNER = "ip"
+
+
+def assign_metric(keys, table, metric):
+    """Assignment under one of the three metrics the paper compares.
+      cosine: argmax_c <k, table_c>, table = unit-length centroids (as `assign`);
+      ip:     argmax_c <k, table_c>, table = the centroids themselves;
+      l2:     argmin_c |k - table_c|^2, table = the centroids themselves.
+    Ties go to the lower id.  Returns (labels, gap): gap = distance between the
+    best and the second-best candidate, expressed in units of <k, .>/|k| so that
+    one tolerance serves all three (l2: half the difference of squared distances)."""
+    keys = np.asarray(keys, dtype=np.float64)
+    table = np.asarray(table, dtype=np.float64)
+    if metric in (COSINE, INNER):
+        labels, _, gap = assign(keys, table)
+        return labels, gap
+    if metric != L2:
+        raise ValueError(metric)
+    n, C = len(keys), len(table)
+    labels = np.zeros(n, dtype=np.int64)
+    gap = np.full(n, np.inf)
+    for lo in range(0, n, 512):                               # key blocks only bound the memory
+        blk = keys[lo:lo + 512]
+        diff = blk[:, None, :] - table[None, :, :]
+        d2 = (diff * diff).sum(axis=2)                        # [block, C]
+        lab = np.argmin(d2, axis=1)                           # first minimum wins
+        labels[lo:lo + 512] = lab
+        if C > 1:
+            part = np.partition(d2, 1, axis=1)
+            knorm = np.sqrt((blk * blk).sum(axis=1))
+            g = 0.5 * (part[:, 1] - part[:, 0])
+            gap[lo:lo + 512] = np.where(knorm > 0, g / np.where(knorm > 0, knorm, 1.0), 0.0)
+    return labels, gap
+
+
+def metric_table(mu, metric, storage):
+    """The centroid table an assignment under `metric` compares the keys with."""
+    return storage_round(unit_rows(mu) if metric == COSINE else mu, storage)
+
+
+def kmeans_run(keys, init_idx, max_iter, storage="bf16", metric=COSINE, until_converged=False):
+    """K-means as in `kmeans`, under any of the three metrics, optionally stopping
+    as soon as an assignment reproduces the labels of the previous one (Section
+    III-B: the two steps alternate until the assignment no longer changes).  The
+    confirming assignment counts as an iteration and is not followed by an update
+    (it would recompute the same means).  Returns (mu, labels, sizes, n_done,
+    trace); trace has the tables, labels, gaps and means of every iteration run."""
+    keys = np.asarray(keys, dtype=np.float64)
+    init_idx = np.asarray(init_idx, dtype=np.int64)
+    rows = keys[init_idx]
+    if len({r.tobytes() for r in rows}) != len(rows):
+        raise ValueError("initial centroids must be distinct key rows")
+    mu = np.array(rows, dtype=np.float64, copy=True)
+    sizes = np.zeros(len(init_idx), dtype=np.int64)
+    labels = None
+    tr = KMeansTrace()
+    n_done = 0
+    for _ in range(max_iter):
+        table = metric_table(mu, metric, storage)
+        new_labels, gap = assign_metric(keys, table, metric)
+        n_done += 1
+        tr.mu_hat.append(table)
+        tr.labels.append(new_labels)
+        tr.gap.append(gap)
+        if until_converged and labels is not None and np.array_equal(new_labels, labels):
+            break
+        labels = new_labels
+        mu, sizes = update(keys, labels, mu)
+        tr.mu.append(mu)
+        tr.sizes.append(sizes)
+    return mu, labels, sizes, n_done, tr
+
+
+def sum_squared_distance(keys, mu, labels):
+    """The textbook K-means objective (l2 metric)."""
+    d = np.asarray(keys, dtype=np.float64) - np.asarray(mu, dtype=np.float64)[labels]
+    return float((d * d).sum())
+
+
+# --------------------------------------------------------------------------
 # clustering metadata (Section IV-C, Fig. 8)
 # --------------------------------------------------------------------------
 def build_metadata(labels, C, tok_begin=0):
@@ -289,3 +377,79 @@ def selection_near_tie(scores, order, n_sel, tol=1e-4):
         if abs(s[j] - s[j + 1]) < tol * (1.0 + abs(s[j])):
             return True
     return False
+
+
+# --------------------------------------------------------------------------
+# evaluation of a selection: exact top-B tokens, recall rate, page selector
+# (Section V-B "recall rate of important tokens"; Section II-C for the
+# page-granular selector the recall curves are compared with)
+# --------------------------------------------------------------------------
+def token_scores(q_group, keys):
+    """Importance of every token for one KV head: the attention logits of the G
+    query heads of the group, summed (Section III-A states the goal as the
+    tokens with the largest q.k; the group sum is the same reading as for the
+    cluster scores)."""
+    q = np.asarray(q_group, dtype=np.float64)
+    return (np.asarray(keys, dtype=np.float64) @ q.T).sum(axis=1)
+
+
+def topk_indices(scores, k):
+    """Indices of the k largest scores (equal scores: the lower index is the
+    larger), returned in ascending index order; all indices if k >= len."""
+    s = np.asarray(scores, dtype=np.float64)
+    k = max(0, min(int(k), len(s)))
+    order = np.argsort(-s, kind="stable")[:k]
+    return np.sort(order).astype(np.int64)
+
+
+def topk_near_tie(scores, k, tol=1e-4):
+    """True when the k-th and (k+1)-th largest scores are closer than
+    tol*(1+|s|): the top-k set may then legitimately differ by rounding."""
+    s = np.sort(np.asarray(scores, dtype=np.float64))[::-1]
+    if k <= 0 or k >= len(s):
+        return False
+    return abs(s[k - 1] - s[k]) < tol * (1.0 + abs(s[k - 1]))
+
+
+def recall_rate(selected, true_set):
+    """|I_T intersect I_true| / |I_true| (Section V-B); 1.0 for an empty I_true."""
+    t = np.unique(np.asarray(true_set, dtype=np.int64))
+    if len(t) == 0:
+        return 1.0
+    sel = np.unique(np.asarray(selected, dtype=np.int64))
+    return len(np.intersect1d(sel, t, assume_unique=True)) / len(t)
+
+
+def page_keys(keys, page_size, tok_begin=0, tok_count=None):
+    """Representative of every page of `page_size` consecutive tokens of
+    [tok_begin, tok_begin + tok_count): the per-channel maximum of its keys, as
+    Section II-C describes the page-granular selector.  The last page may be short."""
+    k = np.asarray(keys, dtype=np.float64)
+    n = (len(k) - tok_begin) if tok_count is None else tok_count
+    n_pages = (n + page_size - 1) // page_size
+    rep = np.empty((n_pages, k.shape[1]))
+    for p in range(n_pages):
+        lo = tok_begin + p * page_size
+        rep[p] = k[lo:min(lo + page_size, tok_begin + n)].max(axis=0)
+    return rep
+
+
+def expand_pages(pages, page_size, n_tokens, tok_begin=0):
+    """Token ids of the given pages (ascending page order, tokens ascending
+    inside a page); the last page stops at tok_begin + n_tokens."""
+    out = []
+    for p in np.sort(np.asarray(pages, dtype=np.int64)):
+        lo = tok_begin + p * page_size
+        out.append(np.arange(lo, min(lo + page_size, tok_begin + n_tokens)))
+    return np.concatenate(out).astype(np.int64) if out else np.zeros(0, dtype=np.int64)
+
+
+def page_select(q_group, keys, page_size, budget, tok_begin=0, tok_count=None):
+    """Page-granular selection: score every page by <sum_g q_g, representative>,
+    keep the budget // page_size best pages, return (pages ascending, token ids)."""
+    k = np.asarray(keys, dtype=np.float64)
+    n = (len(k) - tok_begin) if tok_count is None else tok_count
+    rep = page_keys(k, page_size, tok_begin, n)
+    s = token_scores(q_group, rep)
+    pages = topk_indices(s, budget // page_size)
+    return pages, expand_pages(pages, page_size, n, tok_begin)
