@@ -238,6 +238,83 @@ int ck_decode_step(const ck_shape* sh, const void* q, const void* K, const void*
                    int32_t* n_tokens, void* out, void* workspace, size_t workspace_bytes,
                    void* stream);
 
+/* ------------------------------------------------------------------------
+ * Evaluation of a selection (paper Section V-B, "recall rate of important
+ * tokens") and the full-KV / page-granular comparison points.  Not on the
+ * decode path.  Same conventions as above: device pointers, caller-owned,
+ * enqueue only, host-side validation.
+ * ---------------------------------------------------------------------- */
+
+/*
+ * Full-KV decode attention (Section II-A): softmax(q K^T * softmax_scale) V over
+ * tokens [0, n_ctx) of every head-problem, the computation the compressed path
+ * approximates.  q, K, V, out as in ck_sparse_decode_attn.  workspace: at least
+ * ck_workspace_bytes(sh, CK_WS_SPARSE_ATTN, n_ctx, 0) bytes.
+ * Errors: CK_EINVALID for n_ctx outside [1, N_cap].
+ */
+int ck_full_decode_attn(const ck_shape* sh, const void* q, const void* K, const void* V,
+                        int64_t n_ctx, float softmax_scale, void* out, void* workspace,
+                        size_t workspace_bytes, void* stream);
+
+/*
+ * Exact importance of every token of [tok_begin, tok_begin + tok_count) (Section
+ * III-A: the ideal selection keeps the tokens with the largest q.k): scores[s, h, t]
+ * = sum over the G query heads of the group of <q_g, K[s, h, t]>, fp32, written at
+ * the token's own position in scores [S, Hkv, N_cap] (other positions untouched).
+ * K may be any table of rows laid out [S, Hkv, N_cap, d] in sh->dtype, e.g. the page
+ * representatives of ck_page_keys with N_cap = their row stride.
+ */
+int ck_token_scores(const ck_shape* sh, const void* q, const void* K, int64_t tok_begin,
+                    int64_t tok_count, float* scores, void* stream);
+
+/*
+ * Exact top-k per head-problem over scores[hp * row_stride + begin + i], i < n:
+ * the k largest values (equal values: lower index first; -0 == +0), their indices
+ * begin + i written in ASCENDING INDEX order to out_idx [n_problems, out_stride]
+ * int32; n_out [n_problems] int32 receives min(k, n).  Bit-reproducible.
+ * Errors: CK_EINVALID for n < 1, k < 0, out_stride < min(k, n), n_problems outside
+ * [1, 65535].
+ */
+int ck_topk_select(int32_t n_problems, const float* scores, int64_t row_stride, int64_t begin,
+                   int32_t n, int32_t k, int32_t* out_idx, int32_t out_stride, int32_t* n_out,
+                   void* stream);
+
+/*
+ * Numerator of the recall rate |I_T intersect I_true| / |I_true| (Section V-B):
+ * hits [n_problems] int32 = number of the first n_tokens[p] entries of token_idx
+ * [n_problems, idx_stride] that occur among the first n_ref[p] entries of ref_idx
+ * [n_problems, ref_stride].  ref_idx rows must be ascending and distinct (as
+ * ck_topk_select writes them); token_idx entries are expected to be distinct.
+ */
+int ck_recall_hits(int32_t n_problems, const int32_t* token_idx, const int32_t* n_tokens,
+                   int32_t idx_stride, const int32_t* ref_idx, const int32_t* n_ref,
+                   int32_t ref_stride, int32_t* hits, void* stream);
+
+/*
+ * Page-granular selector of Section II-C, step 1: representative of every page of
+ * page_size consecutive tokens of [tok_begin, tok_begin + tok_count) = per-channel
+ * maximum of its keys (the last page may be short).  page_keys [S, Hkv, page_stride,
+ * d] in sh->dtype; rows [0, ceil(tok_count / page_size)) are written.  Scoring the
+ * pages is ck_token_scores on this table, choosing them ck_topk_select with
+ * k = budget / page_size.
+ * Errors: CK_EINVALID for page_size < 1 or page_stride smaller than the page count.
+ */
+int ck_page_keys(const ck_shape* sh, const void* K, int64_t tok_begin, int64_t tok_count,
+                 int32_t page_size, void* page_keys, int64_t page_stride, void* stream);
+
+/*
+ * Page-granular selector, last step: token ids of the selected pages.  page_idx
+ * [n_problems, page_stride] int32 holds n_pages[p] distinct page numbers in ascending
+ * order (page j covers tokens tok_begin + [j * page_size, (j+1) * page_size), cut
+ * at tok_begin + tok_count).  token_idx [n_problems, idx_stride] receives the ids in
+ * ascending order, n_tokens [n_problems] their count; pages that would not fit
+ * idx_stride are dropped from the end.
+ */
+int ck_expand_pages(int32_t n_problems, const int32_t* page_idx, const int32_t* n_pages,
+                    int32_t page_stride, int32_t page_size, int64_t tok_begin,
+                    int64_t tok_count, int32_t* token_idx, int32_t idx_stride,
+                    int32_t* n_tokens, void* stream);
+
 /*
  * Measurement aid, not part of the method: a register-only loop of
  * v_mfma_f32_32x32x16_bf16 (the instruction the assignment step of Section III-B

@@ -23,7 +23,8 @@ LIB_PATH = os.path.join(_PKG, "libclusterkv.so")
 EXPORTS = ("ck_version", "ck_strerror", "ck_last_error_detail", "ck_workspace_bytes",
            "ck_cluster_keys", "ck_kmeans_assign", "ck_build_metadata", "ck_kmeans_update",
            "ck_select_clusters", "ck_gather_indices", "ck_sparse_decode_attn", "ck_decode_step",
-           "ck_probe_mfma_bf16")
+           "ck_full_decode_attn", "ck_token_scores", "ck_topk_select", "ck_recall_hits",
+           "ck_page_keys", "ck_expand_pages", "ck_probe_mfma_bf16")
 
 
 class ClusterKVError(RuntimeError):
@@ -99,6 +100,18 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.ck_decode_step.restype = ctypes.c_int
     lib.ck_decode_step.argtypes = [SH, P, P, P, P, P, P, P, I32, I32, U32, I64, I64, I64, F,
                                    P, P, P, P, P, I32, P, P, P, SZ, P]
+    lib.ck_full_decode_attn.restype = ctypes.c_int
+    lib.ck_full_decode_attn.argtypes = [SH, P, P, P, I64, F, P, P, SZ, P]
+    lib.ck_token_scores.restype = ctypes.c_int
+    lib.ck_token_scores.argtypes = [SH, P, P, I64, I64, P, P]
+    lib.ck_topk_select.restype = ctypes.c_int
+    lib.ck_topk_select.argtypes = [I32, P, I64, I64, I32, I32, P, I32, P, P]
+    lib.ck_recall_hits.restype = ctypes.c_int
+    lib.ck_recall_hits.argtypes = [I32, P, P, I32, P, P, I32, P, P]
+    lib.ck_page_keys.restype = ctypes.c_int
+    lib.ck_page_keys.argtypes = [SH, P, I64, I64, I32, P, I64, P]
+    lib.ck_expand_pages.restype = ctypes.c_int
+    lib.ck_expand_pages.argtypes = [I32, P, P, I32, I32, I64, I64, P, I32, P, P]
     lib.ck_probe_mfma_bf16.restype = ctypes.c_int
     lib.ck_probe_mfma_bf16.argtypes = [I32, I32, P, ctypes.POINTER(ctypes.c_double), P]
     _lib = lib
@@ -225,6 +238,60 @@ def ck_sparse_decode_attn(sh: Shape, q, K, V, token_idx, n_tokens, max_tokens, o
                                      workspace.numel() if isinstance(workspace, torch.Tensor)
                                      else 0, _stream(q)))
     return workspace
+
+
+def ck_full_decode_attn(sh: Shape, q, K, V, n_ctx, out, softmax_scale=None, workspace=None):
+    lib = load_library()
+    if softmax_scale is None:
+        softmax_scale = sh.d ** -0.5
+    if workspace is None:
+        workspace = _workspace(ck_workspace_bytes(sh, CK_WS_SPARSE_ATTN, n_ctx), q)
+    s = sh.c()
+    _check(lib.ck_full_decode_attn(ctypes.byref(s), _ptr(q), _ptr(K), _ptr(V), n_ctx,
+                                   softmax_scale, _ptr(out), _ptr(workspace),
+                                   workspace.numel() if isinstance(workspace, torch.Tensor)
+                                   else 0, _stream(q)))
+    return workspace
+
+
+def ck_token_scores(sh: Shape, q, K, tok_begin, tok_count, scores):
+    lib = load_library()
+    s = sh.c()
+    _check(lib.ck_token_scores(ctypes.byref(s), _ptr(q), _ptr(K), tok_begin, tok_count,
+                               _ptr(scores), _stream(q)))
+
+
+def ck_topk_select(n_problems, scores, row_stride, begin, n, k, out_idx, n_out):
+    lib = load_library()
+    stride = out_idx.shape[-1] if isinstance(out_idx, torch.Tensor) else max(1, min(k, n))
+    _check(lib.ck_topk_select(n_problems, _ptr(scores), row_stride, begin, n, k, _ptr(out_idx),
+                              stride, _ptr(n_out), _stream(scores)))
+
+
+def ck_recall_hits(n_problems, token_idx, n_tokens, ref_idx, n_ref, hits):
+    lib = load_library()
+    istride = token_idx.shape[-1] if isinstance(token_idx, torch.Tensor) else 1
+    rstride = ref_idx.shape[-1] if isinstance(ref_idx, torch.Tensor) else 1
+    _check(lib.ck_recall_hits(n_problems, _ptr(token_idx), _ptr(n_tokens), istride, _ptr(ref_idx),
+                              _ptr(n_ref), rstride, _ptr(hits), _stream(token_idx)))
+
+
+def ck_page_keys(sh: Shape, K, tok_begin, tok_count, page_size, page_keys):
+    lib = load_library()
+    stride = page_keys.shape[-2] if isinstance(page_keys, torch.Tensor) else 0
+    s = sh.c()
+    _check(lib.ck_page_keys(ctypes.byref(s), _ptr(K), tok_begin, tok_count, page_size,
+                            _ptr(page_keys), stride, _stream(K)))
+
+
+def ck_expand_pages(n_problems, page_idx, n_pages, page_size, tok_begin, tok_count, token_idx,
+                    n_tokens):
+    lib = load_library()
+    pstride = page_idx.shape[-1] if isinstance(page_idx, torch.Tensor) else 1
+    istride = token_idx.shape[-1] if isinstance(token_idx, torch.Tensor) else 1
+    _check(lib.ck_expand_pages(n_problems, _ptr(page_idx), _ptr(n_pages), pstride, page_size,
+                               tok_begin, tok_count, _ptr(token_idx), istride, _ptr(n_tokens),
+                               _stream(page_idx)))
 
 
 def ck_probe_mfma_bf16(n_workgroups: int, iters: int, sink) -> float:

@@ -364,6 +364,126 @@ int ck_decode_step(const ck_shape* sh, const void* q, const void* K, const void*
       "fused decode launch");
 }
 
+int ck_full_decode_attn(const ck_shape* sh, const void* q, const void* K, const void* V,
+                        int64_t n_ctx, float softmax_scale, void* out, void* workspace,
+                        size_t workspace_bytes, void* stream) {
+  ck::Dims dm;
+  int rc = check_shape(sh, &dm, false);
+  if (rc) return rc;
+  if (n_ctx < 1 || n_ctx > sh->N_cap)
+    return fail(CK_EINVALID, "n_ctx=%lld outside [1, N_cap]", (long long)n_ctx);
+  if (n_ctx > (int64_t)1 << 30) return fail(CK_EUNSUPPORTED, "attended set too large");
+  if (!(softmax_scale > 0.f)) return fail(CK_EINVALID, "softmax_scale must be positive");
+  CK_REQUIRE_PTR(q);
+  CK_REQUIRE_PTR(K);
+  CK_REQUIRE_PTR(V);
+  CK_REQUIRE_PTR(out);
+  const size_t need = ck::attn_workspace_bytes(dm, n_ctx);
+  if (!workspace) return fail(CK_EWORKSPACE, "workspace is NULL");
+  if (!aligned16(workspace)) return fail(CK_EMISALIGNED, "workspace is not 16-byte aligned");
+  if (workspace_bytes < need)
+    return fail(CK_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+  // the leading "sink" range of the attended set, stretched over the whole context
+  return hip_result(ck::launch_sparse_attn(dm, q, K, V, nullptr, nullptr, 0, n_ctx, n_ctx, 0, 0,
+                                           softmax_scale, out, workspace, (hipStream_t)stream),
+                    "full attention launch");
+}
+
+int ck_token_scores(const ck_shape* sh, const void* q, const void* K, int64_t tok_begin,
+                    int64_t tok_count, float* scores, void* stream) {
+  ck::Dims dm;
+  int rc = check_shape(sh, &dm, false);
+  if (rc) return rc;
+  if (tok_begin < 0 || tok_count < 1 || tok_begin + tok_count > sh->N_cap)
+    return fail(CK_EINVALID, "token range [%lld, +%lld) outside [0, %lld]", (long long)tok_begin,
+                (long long)tok_count, (long long)sh->N_cap);
+  CK_REQUIRE_PTR(q);
+  CK_REQUIRE_PTR(K);
+  CK_REQUIRE_PTR(scores);
+  return hip_result(ck::launch_row_scores(dm, q, K, dm.N_cap, tok_begin, (int)tok_count, scores,
+                                          dm.N_cap, (hipStream_t)stream),
+                    "token score launch");
+}
+
+int ck_topk_select(int32_t n_problems, const float* scores, int64_t row_stride, int64_t begin,
+                   int32_t n, int32_t k, int32_t* out_idx, int32_t out_stride, int32_t* n_out,
+                   void* stream) {
+  if (n_problems < 1 || n_problems > 65535)
+    return fail(CK_EINVALID, "n_problems=%d outside [1, 65535]", n_problems);
+  if (n < 1 || k < 0) return fail(CK_EINVALID, "n=%d must be positive and k=%d non-negative", n, k);
+  if (begin < 0 || row_stride < begin + n)
+    return fail(CK_EINVALID, "range [%lld, +%d) outside a row of %lld", (long long)begin, n,
+                (long long)row_stride);
+  if (begin + n > (int64_t)0x7FFFFFFF) return fail(CK_EUNSUPPORTED, "indices exceed int32");
+  if (out_stride < (k < n ? k : n))
+    return fail(CK_EINVALID, "out_stride=%d smaller than min(k, n)", out_stride);
+  CK_REQUIRE_PTR(scores);
+  CK_REQUIRE_PTR(out_idx);
+  CK_REQUIRE_PTR(n_out);
+  return hip_result(ck::launch_topk(n_problems, scores, row_stride, begin, n, k, out_idx,
+                                    out_stride, n_out, (hipStream_t)stream),
+                    "top-k launch");
+}
+
+int ck_recall_hits(int32_t n_problems, const int32_t* token_idx, const int32_t* n_tokens,
+                   int32_t idx_stride, const int32_t* ref_idx, const int32_t* n_ref,
+                   int32_t ref_stride, int32_t* hits, void* stream) {
+  if (n_problems < 1 || n_problems > 65535)
+    return fail(CK_EINVALID, "n_problems=%d outside [1, 65535]", n_problems);
+  if (idx_stride < 1 || ref_stride < 1)
+    return fail(CK_EINVALID, "idx_stride=%d and ref_stride=%d must be positive", idx_stride,
+                ref_stride);
+  CK_REQUIRE_PTR(token_idx);
+  CK_REQUIRE_PTR(n_tokens);
+  CK_REQUIRE_PTR(ref_idx);
+  CK_REQUIRE_PTR(n_ref);
+  CK_REQUIRE_PTR(hits);
+  return hip_result(ck::launch_recall_hits(n_problems, token_idx, n_tokens, idx_stride, ref_idx,
+                                           n_ref, ref_stride, hits, (hipStream_t)stream),
+                    "recall launch");
+}
+
+int ck_page_keys(const ck_shape* sh, const void* K, int64_t tok_begin, int64_t tok_count,
+                 int32_t page_size, void* page_keys, int64_t page_stride, void* stream) {
+  ck::Dims dm;
+  int rc = check_shape(sh, &dm, false);
+  if (rc) return rc;
+  if (tok_begin < 0 || tok_count < 1 || tok_begin + tok_count > sh->N_cap)
+    return fail(CK_EINVALID, "token range [%lld, +%lld) outside [0, %lld]", (long long)tok_begin,
+                (long long)tok_count, (long long)sh->N_cap);
+  if (page_size < 1) return fail(CK_EINVALID, "page_size=%d must be positive", page_size);
+  const int64_t n_pages = (tok_count + page_size - 1) / page_size;
+  if (page_stride < n_pages)
+    return fail(CK_EINVALID, "page_stride=%lld smaller than the %lld pages", (long long)page_stride,
+                (long long)n_pages);
+  CK_REQUIRE_PTR(K);
+  CK_REQUIRE_PTR(page_keys);
+  return hip_result(ck::launch_page_keys(dm, K, tok_begin, tok_count, page_size, page_keys,
+                                         page_stride, (hipStream_t)stream),
+                    "page representative launch");
+}
+
+int ck_expand_pages(int32_t n_problems, const int32_t* page_idx, const int32_t* n_pages,
+                    int32_t page_stride, int32_t page_size, int64_t tok_begin,
+                    int64_t tok_count, int32_t* token_idx, int32_t idx_stride,
+                    int32_t* n_tokens, void* stream) {
+  if (n_problems < 1 || n_problems > 65535)
+    return fail(CK_EINVALID, "n_problems=%d outside [1, 65535]", n_problems);
+  if (page_size < 1 || page_stride < 1 || idx_stride < 1)
+    return fail(CK_EINVALID, "page_size, page_stride and idx_stride must be positive");
+  if (tok_begin < 0 || tok_count < 1 || tok_begin + tok_count > (int64_t)0x7FFFFFFF)
+    return fail(CK_EINVALID, "token range [%lld, +%lld) invalid", (long long)tok_begin,
+                (long long)tok_count);
+  CK_REQUIRE_PTR(page_idx);
+  CK_REQUIRE_PTR(n_pages);
+  CK_REQUIRE_PTR(token_idx);
+  CK_REQUIRE_PTR(n_tokens);
+  return hip_result(ck::launch_expand_pages(n_problems, page_idx, n_pages, page_stride, page_size,
+                                            tok_begin, tok_count, token_idx, idx_stride, n_tokens,
+                                            (hipStream_t)stream),
+                    "page expansion launch");
+}
+
 int ck_probe_mfma_bf16(int32_t n_workgroups, int32_t iters, float* sink, double* flops,
                        void* stream) {
   if (n_workgroups < 1 || n_workgroups > 65535 || iters < 1 || iters > (1 << 24))

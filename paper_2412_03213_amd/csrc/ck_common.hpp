@@ -175,6 +175,21 @@ hipError_t launch_gather(const Dims& dm, const int32_t* sel_clusters,
                          const int32_t* sorted_idx, int budget, uint32_t flags,
                          int32_t* token_idx, int idx_stride, int32_t* n_tokens, hipStream_t st);
 hipError_t launch_probe_mfma(int n_workgroups, int iters, float* sink, hipStream_t st);
+// evaluation helpers
+hipError_t launch_row_scores(const Dims& dm, const void* q, const void* table,
+                             int64_t table_stride, int64_t row_begin, int n_rows, float* scores,
+                             int64_t score_stride, hipStream_t st);
+hipError_t launch_topk(int HP, const float* scores, int64_t row_stride, int64_t begin, int n,
+                       int k, int32_t* out_idx, int out_stride, int32_t* n_out, hipStream_t st);
+hipError_t launch_recall_hits(int HP, const int32_t* token_idx, const int32_t* n_tokens,
+                              int idx_stride, const int32_t* ref_idx, const int32_t* n_ref,
+                              int ref_stride, int32_t* hits, hipStream_t st);
+hipError_t launch_page_keys(const Dims& dm, const void* K, int64_t tok_begin, int64_t tok_count,
+                            int page_size, void* page_keys, int64_t page_stride, hipStream_t st);
+hipError_t launch_expand_pages(int HP, const int32_t* page_idx, const int32_t* n_pages_sel,
+                               int page_stride, int page_size, int64_t tok_begin,
+                               int64_t tok_count, int32_t* token_idx, int idx_stride,
+                               int32_t* n_tokens, hipStream_t st);
 int attn_num_splits(const Dims& dm, int64_t max_total);
 size_t attn_workspace_bytes(const Dims& dm, int64_t max_total);
 hipError_t launch_sparse_attn(const Dims& dm, const void* q, const void* K, const void* V,

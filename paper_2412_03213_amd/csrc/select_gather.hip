@@ -14,18 +14,19 @@ constexpr int SCORE_THREADS = 256;
 // workgroup, fewer workgroups to dispatch).
 template <typename T, int SCORE_ROWS>
 __global__ __launch_bounds__(SCORE_THREADS) void k_score(
-    const T* __restrict__ q, const T* __restrict__ centroids, int Hq, int Hkv, int G, int C_cap,
-    int n_clusters, float* __restrict__ scores) {
+    const T* __restrict__ q, const T* __restrict__ table, int Hq, int Hkv, int G,
+    int64_t table_stride, int64_t row_begin, int n_rows, float* __restrict__ scores,
+    int64_t score_stride) {
   const int hp = blockIdx.y, tid = threadIdx.x;
   const int s = hp / Hkv, h = hp % Hkv;
   const int l16 = tid & 15, grp = tid >> 4;                 // 16 groups of 16 lanes
   const int c0 = blockIdx.x * SCORE_ROWS;
-  const T* Chp = centroids + (int64_t)hp * C_cap * D + l16 * 8;
+  const T* Chp = table + ((int64_t)hp * table_stride + row_begin) * D + l16 * 8;
   float mv[SCORE_ROWS / 16][8];
 #pragma unroll
   for (int u = 0; u < SCORE_ROWS / 16; ++u) {
     int c = c0 + u * 16 + grp;
-    if (c >= n_clusters) c = n_clusters - 1;               // clamp: result is discarded
+    if (c >= n_rows) c = n_rows - 1;                       // clamp: result is discarded
     load_row8<T>(Chp + (int64_t)c * D, mv[u]);
   }
   float qv[8];
@@ -44,18 +45,23 @@ __global__ __launch_bounds__(SCORE_THREADS) void k_score(
 #pragma unroll
     for (int j = 0; j < 8; ++j) dot = fmaf(qv[j], mv[u][j], dot);
     dot = row16_sum(dot);
-    if (c < n_clusters && l16 == 0) scores[(int64_t)hp * C_cap + c] = dot;
+    if (c < n_rows && l16 == 0) scores[(int64_t)hp * score_stride + row_begin + c] = dot;
   }
 }
 
-hipError_t launch_score(const Dims& dm, const void* q, const void* centroids, int n_clusters,
-                        float* scores, hipStream_t st) {
-  const bool many = (int64_t)dm.HP * ((n_clusters + 63) / 64) > 2048;
+// scores[hp, row_begin + r] = <sum_g q_g, table[hp, row_begin + r]> for r < n_rows: the
+// centroid table of a decode step, or any other row table laid out per head-problem
+// (the keys themselves for exact token importance, page representatives).
+hipError_t launch_row_scores(const Dims& dm, const void* q, const void* table,
+                             int64_t table_stride, int64_t row_begin, int n_rows, float* scores,
+                             int64_t score_stride, hipStream_t st) {
+  const bool many = (int64_t)dm.HP * ((n_rows + 63) / 64) > 2048;
   const int rows = many ? 256 : 64;
-  const dim3 grid((n_clusters + rows - 1) / rows, dm.HP);
+  const dim3 grid((n_rows + rows - 1) / rows, dm.HP);
 #define CK_SCORE(TT, RR)                                                                    \
   hipLaunchKernelGGL((k_score<TT, RR>), grid, dim3(SCORE_THREADS), 0, st, (const TT*)q,     \
-                     (const TT*)centroids, dm.Hq, dm.Hkv, dm.G, dm.C_cap, n_clusters, scores)
+                     (const TT*)table, dm.Hq, dm.Hkv, dm.G, table_stride, row_begin, n_rows, \
+                     scores, score_stride)
   if (dm.dtype == CK_BF16) {
     if (many) CK_SCORE(bf16, 256); else CK_SCORE(bf16, 64);
   } else {
@@ -63,6 +69,11 @@ hipError_t launch_score(const Dims& dm, const void* q, const void* centroids, in
   }
 #undef CK_SCORE
   return hipGetLastError();
+}
+
+hipError_t launch_score(const Dims& dm, const void* q, const void* centroids, int n_clusters,
+                        float* scores, hipStream_t st) {
+  return launch_row_scores(dm, q, centroids, dm.C_cap, 0, n_clusters, scores, dm.C_cap, st);
 }
 
 // ------------------------------------------------------------------ order + budget

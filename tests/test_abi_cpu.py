@@ -142,7 +142,26 @@ def test_argument_validation_without_a_device():
     expect(-3, attn, wsb=8)
     expect(-3, attn, ws=None)
     expect(-4, attn, V=A + 2)
-    assert "workspace" in lib.ck_last_error_detail().decode() or True
+
+    # evaluation entry points
+    expect(-1, ck.ck_full_decode_attn, sh, A, A, A, 0, A, workspace=A)
+    expect(-1, ck.ck_full_decode_attn, sh, A, A, A, 1001, A, workspace=A)
+    expect(-1, ck.ck_full_decode_attn, sh, A, A, None, 1000, A, workspace=A)
+    expect(-3, ck.ck_full_decode_attn, sh, A, A, A, 1000, A, workspace=0)
+    expect(-1, ck.ck_token_scores, sh, A, A, 0, 1001, A)
+    expect(-1, ck.ck_token_scores, sh, A, A, 0, 1000, None)
+    expect(-4, ck.ck_token_scores, sh, A, A + 4, 0, 1000, A)
+    expect(-1, ck.ck_topk_select, 0, A, 1000, 0, 1000, 10, A, A)
+    expect(-1, ck.ck_topk_select, 8, A, 1000, 0, 0, 10, A, A)
+    expect(-1, ck.ck_topk_select, 8, A, 1000, 0, 1000, -1, A, A)
+    expect(-1, ck.ck_topk_select, 8, A, 1000, 1, 1000, 10, A, A)        # range leaves the row
+    expect(-1, ck.ck_topk_select, 8, A, 1000, 0, 1000, 10, A, None)
+    expect(-1, ck.ck_recall_hits, 8, A, A, A, None, A)
+    expect(-1, ck.ck_recall_hits, 70000, A, A, A, A, A)
+    expect(-1, ck.ck_page_keys, sh, A, 0, 1000, 0, A)                   # page_size 0, stride 0
+    expect(-1, ck.ck_page_keys, sh, A, 0, 1001, 16, A)
+    expect(-1, ck.ck_expand_pages, 8, A, A, 0, 0, 1000, A, A)
+    expect(-1, ck.ck_expand_pages, 8, A, None, 16, 0, 1000, A, A)
 
 
 def test_missing_library_is_an_error(monkeypatch, tmp_path):
