@@ -38,6 +38,8 @@ def parse():
                     help="skip the 1024-step decode loop with incremental clustering (batch 16)")
     ap.add_argument("--no-long-context", action="store_true",
                     help="skip the 128k-context leg (C=1600: K-means + one decode step)")
+    ap.add_argument("--no-recall", action="store_true",
+                    help="skip the recall-rate curves (cluster vs page selection vs exact top-B)")
     ap.add_argument("--full-depth", action="store_true",
                     help="also run all 32 layers x 8 sequences of the full-depth configuration "
                          "as one batch of 2048 head-problems (needs ~36 GiB of HBM)")
@@ -268,6 +270,18 @@ def main():
 
     at_avg, at_med, at_min = per_launch_ms(attn, 10 * reps)
 
+    # the computation the path approximates: decode attention over the whole KV cache
+    full_out = torch.empty_like(st.out)
+    full_ws = torch.empty(ck.ck_workspace_bytes(sh, 1, cfg.N), dtype=torch.uint8, device=dev)
+
+    def full_attn():
+        ck.ck_full_decode_attn(sh, q, w.K, w.V, cfg.N, full_out, workspace=full_ws)
+
+    for _ in range(3):
+        full_attn()
+    full_ms = event_ms(full_attn, 5 * reps)
+    full_bytes = 2.0 * HP * cfg.N * cfg.d * 2
+
     result = {
         "metric": "decode us/layer & recalled-KV GB/s at 32k ctx, B=1024; K-means keys/s",
         "value": keys_per_step / (ms_per_step * 1e-3),
@@ -305,6 +319,13 @@ def main():
                             "note": "batch 1: 8 head-problems, launch-latency bound"},
     }
 
+    result["full_kv_decode"] = {
+        "us_per_layer": full_ms * 1e3, "GBps": full_bytes / (full_ms * 1e-3) / 1e9,
+        "frac_of_hbm_peak": full_bytes / (full_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS,
+        "speedup_of_compressed_decode": full_ms / decode_ms,
+        "note": "ck_full_decode_attn over all N tokens of the same layer (split-KV + merge)"}
+    if not args.no_recall:
+        result["recall_rate"] = recall_curves(cfg, w, st, sh)
     result["measured_peaks"] = measured_peaks(dev)
     if not args.no_batch8:
         result["decode_batch8_B2048"] = big_decode(reps, layers=1)
@@ -325,6 +346,60 @@ def main():
     dst.copy_(src)
     torch.cuda.synchronize()
     print(json.dumps(result))
+
+
+def recall_curves(cfg, w, st, sh, n_queries=8, page_size=16):
+    """Recall rate |I_T & I_true| / B against the exact top-B tokens (by summed q.k of the
+    group), averaged over head-problems and queries, for budgets 256..2048: the cluster
+    selection of the clustered state `st` in both budget modes, and the page-granular
+    selector.  All selections, the exact top-B and the hit counts run in the library."""
+    import torch
+    import paper_2412_03213_amd as ck
+    dev = w.K.device
+    HP, N = cfg.S * cfg.Hkv, cfg.N
+    budgets = list(range(256, 2049, 256))
+    n_pages = (N + page_size - 1) // page_size
+    pk = torch.empty(cfg.S, cfg.Hkv, n_pages, cfg.d, dtype=w.K.dtype, device=dev)
+    ck.ck_page_keys(sh, w.K, 0, N, page_size, pk)
+    shp = ck.Shape(cfg.S, cfg.Hq, cfg.Hkv, n_pages, sh.C_cap)
+    tscore = torch.empty(cfg.S, cfg.Hkv, N, dtype=torch.float32, device=dev)
+    pscore = torch.empty(cfg.S, cfg.Hkv, n_pages, dtype=torch.float32, device=dev)
+    cscore = torch.empty(cfg.S, cfg.Hkv, sh.C_cap, dtype=torch.float32, device=dev)
+    sel = torch.empty(cfg.S, cfg.Hkv, sh.C_cap, dtype=torch.int32, device=dev)
+    nsel = torch.empty(HP, dtype=torch.int32, device=dev)
+    nseltok = torch.empty(HP, dtype=torch.int32, device=dev)
+    ntok = torch.empty(HP, dtype=torch.int32, device=dev)
+    nref = torch.empty(HP, dtype=torch.int32, device=dev)
+    npg = torch.empty(HP, dtype=torch.int32, device=dev)
+    hits = torch.empty(HP, dtype=torch.int32, device=dev)
+    acc = {"clusterkv_trim_last": [0.0] * len(budgets), "clusterkv_whole": [0.0] * len(budgets),
+           f"page{page_size}": [0.0] * len(budgets)}
+    for _ in range(n_queries):
+        q = w.query()
+        ck.ck_token_scores(sh, q, w.K, 0, N, tscore)
+        ck.ck_token_scores(shp, q, pk, 0, n_pages, pscore)
+        for bi, B in enumerate(budgets):
+            ref = torch.empty(HP, B, dtype=torch.int32, device=dev)
+            tok = torch.empty(HP, B, dtype=torch.int32, device=dev)
+            ck.ck_topk_select(HP, tscore, N, 0, N, B, ref, nref)
+            for name, mode in (("clusterkv_trim_last", ck.CK_SEL_TRIM_LAST),
+                               ("clusterkv_whole", ck.CK_SEL_WHOLE)):
+                ck.ck_select_clusters(sh, q, st.centroids, st.sizes, st.n_clusters, B, mode, sel,
+                                      nsel, nseltok, cscore)
+                ck.ck_gather_indices(sh, sel, nsel, st.offsets, st.sorted_idx, B, mode, tok, ntok)
+                ck.ck_recall_hits(HP, tok, ntok, ref, nref, hits)
+                acc[name][bi] += float(hits.sum()) / (HP * B)
+            pidx = torch.empty(HP, B // page_size, dtype=torch.int32, device=dev)
+            ck.ck_topk_select(HP, pscore, n_pages, 0, n_pages, B // page_size, pidx, npg)
+            ck.ck_expand_pages(HP, pidx, npg, page_size, 0, N, tok, ntok)
+            ck.ck_recall_hits(HP, tok, ntok, ref, nref, hits)
+            acc[f"page{page_size}"][bi] += float(hits.sum()) / (HP * B)
+    out = {"budgets": budgets, "queries": n_queries, "head_problems": HP,
+           "note": "synthetic mixture keys; I_true = exact top-B by the group's summed q.k; "
+                   "trim_last recalls exactly B tokens, whole clusters at most B"}
+    for k, v in acc.items():
+        out[k] = [round(x / n_queries, 4) for x in v]
+    return out
 
 
 def long_context(reps):
@@ -369,7 +444,19 @@ def long_context(reps):
     d_ms = event_ms(decode, 10 * reps)
     db = decode_bytes(cfg, st, cfg.C)
     tf = flops / (a_ms * 1e-3) / 1e12
+    full_out = torch.empty_like(st.out)
+    full_ws = torch.empty(ck.ck_workspace_bytes(sh, 1, cfg.N), dtype=torch.uint8, device=dev)
+
+    def full_attn():
+        ck.ck_full_decode_attn(sh, q, w.K, w.V, cfg.N, full_out, workspace=full_ws)
+
+    for _ in range(3):
+        full_attn()
+    f_ms = event_ms(full_attn, 2 * reps)
     return {"workload": f"{cfg.name}: N={cfg.N}, C={cfg.C}, B={cfg.B}, {HP} head-problems",
+            "full_kv_decode_us": f_ms * 1e3,
+            "full_kv_GBps": 2.0 * HP * cfg.N * cfg.d * 2 / (f_ms * 1e-3) / 1e9,
+            "speedup_of_compressed_decode": f_ms / d_ms,
             "kmeans_ms": km, "kmeans_keys_per_s": HP * cfg.N / (km * 1e-3),
             "roofline_assign": {"bound": "mfma", "achieved": tf, "peak": PEAK_BF16_MFMA_TFLOPS,
                                 "unit": "TFLOP/s", "frac": tf / PEAK_BF16_MFMA_TFLOPS,
