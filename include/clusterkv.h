@@ -65,6 +65,13 @@ extern "C" {
 
 #define CK_MAX_CLUSTERS 2048
 
+/* flags of ck_cluster_keys_opt */
+#define CK_METRIC_COSINE 0u
+#define CK_METRIC_L2 1u
+#define CK_METRIC_IP 2u
+#define CK_METRIC_MASK 3u
+#define CK_KM_UNTIL_CONVERGED 4u
+
 /* which = argument of ck_workspace_bytes */
 #define CK_WS_CLUSTER_KEYS 0
 #define CK_WS_SPARSE_ATTN 1
@@ -125,6 +132,30 @@ int ck_cluster_keys(const ck_shape* sh, const void* K, int64_t tok_begin, int64_
                     int32_t c_begin, int32_t c_count, int32_t n_iter, const int32_t* init_idx,
                     void* centroids, int32_t* labels, int32_t* sizes, int32_t* offsets,
                     int32_t* sorted_idx, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * ck_cluster_keys with the options the paper discusses beside its default:
+ *   flags & CK_METRIC_MASK   distance of the assignment step (Section V-B compares the
+ *       three): CK_METRIC_COSINE (largest cosine similarity, the default),
+ *       CK_METRIC_L2 (smallest Euclidean distance to the stored centroid) or
+ *       CK_METRIC_IP (largest inner product with the stored centroid).  The update
+ *       step is the mean of the assigned keys under every metric.
+ *   flags & CK_KM_UNTIL_CONVERGED   stop a head-problem at the first assignment that
+ *       changes no label (Section III-B: the two steps alternate until convergence);
+ *       max_iter (<= 256 in this mode) bounds the iterations.  The confirming
+ *       assignment counts as an iteration and is not followed by an update.  Each
+ *       head-problem stops on its own; there is no host synchronisation, iterations
+ *       of stopped head-problems are launches that return at once.
+ * iters_done [dev] int32 [S, Hkv], nullable: iterations each head-problem ran.
+ * Everything else as ck_cluster_keys (which is this call with flags = 0).
+ * Errors: additionally CK_EINVALID for unknown flag bits, CK_EUNSUPPORTED for
+ *   max_iter > 256 with CK_KM_UNTIL_CONVERGED.
+ */
+int ck_cluster_keys_opt(const ck_shape* sh, const void* K, int64_t tok_begin, int64_t tok_count,
+                        int32_t c_begin, int32_t c_count, int32_t max_iter, uint32_t flags,
+                        const int32_t* init_idx, void* centroids, int32_t* labels, int32_t* sizes,
+                        int32_t* offsets, int32_t* sorted_idx, int32_t* iters_done,
+                        void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * The three steps ck_cluster_keys iterates, exported so that each can be checked

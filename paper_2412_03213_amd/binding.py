@@ -15,13 +15,14 @@ import torch
 CK_BF16, CK_F32 = 0, 1
 CK_SEL_WHOLE, CK_SEL_TRIM_LAST = 0, 1
 CK_MAX_CLUSTERS = 2048
+CK_METRIC_COSINE, CK_METRIC_L2, CK_METRIC_IP, CK_KM_UNTIL_CONVERGED = 0, 1, 2, 4
 CK_WS_CLUSTER_KEYS, CK_WS_SPARSE_ATTN = 0, 1
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libclusterkv.so")
 
 EXPORTS = ("ck_version", "ck_strerror", "ck_last_error_detail", "ck_workspace_bytes",
-           "ck_cluster_keys", "ck_kmeans_assign", "ck_build_metadata", "ck_kmeans_update",
+           "ck_cluster_keys", "ck_cluster_keys_opt", "ck_kmeans_assign", "ck_build_metadata", "ck_kmeans_update",
            "ck_select_clusters", "ck_gather_indices", "ck_sparse_decode_attn", "ck_decode_step",
            "ck_full_decode_attn", "ck_token_scores", "ck_topk_select", "ck_recall_hits",
            "ck_page_keys", "ck_expand_pages", "ck_probe_mfma_bf16")
@@ -84,6 +85,9 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.ck_workspace_bytes.argtypes = [SH, ctypes.c_int, I64, I32]
     lib.ck_cluster_keys.restype = ctypes.c_int
     lib.ck_cluster_keys.argtypes = [SH, P, I64, I64, I32, I32, I32, P, P, P, P, P, P, P, SZ, P]
+    lib.ck_cluster_keys_opt.restype = ctypes.c_int
+    lib.ck_cluster_keys_opt.argtypes = [SH, P, I64, I64, I32, I32, I32, U32, P, P, P, P, P, P, P,
+                                        P, SZ, P]
     lib.ck_kmeans_assign.restype = ctypes.c_int
     lib.ck_kmeans_assign.argtypes = [SH, P, I64, I64, P, I32, I32, P, P, P]
     lib.ck_build_metadata.restype = ctypes.c_int
@@ -165,6 +169,22 @@ def ck_cluster_keys(sh: Shape, K, tok_begin, tok_count, c_begin, c_count, n_iter
                                _ptr(sizes), _ptr(offsets), _ptr(sorted_idx), _ptr(workspace),
                                workspace.numel() if isinstance(workspace, torch.Tensor) else 0,
                                _stream(K)))
+    return workspace
+
+
+def ck_cluster_keys_opt(sh: Shape, K, tok_begin, tok_count, c_begin, c_count, max_iter, flags,
+                        init_idx, centroids, labels, sizes, offsets, sorted_idx, iters_done=None,
+                        workspace=None):
+    lib = load_library()
+    if workspace is None:
+        workspace = _workspace(ck_workspace_bytes(sh, CK_WS_CLUSTER_KEYS, tok_count, c_count), K)
+    s = sh.c()
+    _check(lib.ck_cluster_keys_opt(ctypes.byref(s), _ptr(K), tok_begin, tok_count, c_begin,
+                                   c_count, max_iter, flags, _ptr(init_idx), _ptr(centroids),
+                                   _ptr(labels), _ptr(sizes), _ptr(offsets), _ptr(sorted_idx),
+                                   _ptr(iters_done), _ptr(workspace),
+                                   workspace.numel() if isinstance(workspace, torch.Tensor)
+                                   else 0, _stream(K)))
     return workspace
 
 
@@ -332,13 +352,14 @@ class ClusterState:
             self.centroids)
         self.cluster_ws = None
 
-    def cluster(self, K, init_idx, tok_begin, tok_count, c_count, n_iter):
+    def cluster(self, K, init_idx, tok_begin, tok_count, c_count, n_iter, flags=0,
+                iters_done=None):
         need = ck_workspace_bytes(self.sh, CK_WS_CLUSTER_KEYS, tok_count, c_count)
         if self.cluster_ws is None or self.cluster_ws.numel() < need:
             self.cluster_ws = _workspace(need, K)
-        ck_cluster_keys(self.sh, K, tok_begin, tok_count, self.n_clusters, c_count, n_iter,
-                        init_idx, self.centroids, self.labels, self.sizes, self.offsets,
-                        self.sorted_idx, self.cluster_ws)
+        ck_cluster_keys_opt(self.sh, K, tok_begin, tok_count, self.n_clusters, c_count, n_iter,
+                            flags, init_idx, self.centroids, self.labels, self.sizes,
+                            self.offsets, self.sorted_idx, iters_done, self.cluster_ws)
         self.n_clusters += c_count
 
 

@@ -125,7 +125,7 @@ int ck_kmeans_assign(const ck_shape* sh, const void* K, int64_t tok_begin, int64
   CK_OPTIONAL_PTR(best_sim);
   return hip_result(ck::launch_assign(dm, (const ck::bf16*)K, tok_begin, tok_count,
                                       (const ck::bf16*)centroids_hat, c_begin, c_count, labels,
-                                      best_sim, nullptr, (hipStream_t)stream),
+                                      best_sim, nullptr, ck::KmCtl(), (hipStream_t)stream),
                     "assignment launch");
 }
 
@@ -147,7 +147,7 @@ int ck_build_metadata(const ck_shape* sh, const int32_t* labels, int64_t tok_beg
   if (workspace_bytes < ws.bytes)
     return fail(CK_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, ws.bytes);
   return hip_result(ck::launch_metadata(dm, labels, tok_begin, tok_count, c_begin, c_count, sizes,
-                                        offsets, sorted_idx, ws.chunk_hist, false,
+                                        offsets, sorted_idx, ws.chunk_hist, false, nullptr,
                                         (hipStream_t)stream),
                     "metadata launch");
 }
@@ -171,19 +171,28 @@ int ck_kmeans_update(const ck_shape* sh, const void* K, const int32_t* sizes,
   CK_OPTIONAL_PTR(centroids_f32);
   return hip_result(ck::launch_update(dm, (const ck::bf16*)K, offsets, sorted_idx, c_begin,
                                       c_count, (ck::bf16*)centroids, (ck::bf16*)centroids_hat,
-                                      centroids_f32, (hipStream_t)stream),
+                                      centroids_f32, CK_METRIC_COSINE, nullptr, 0, nullptr,
+                                      (hipStream_t)stream),
                     "update launch");
 }
 
-int ck_cluster_keys(const ck_shape* sh, const void* K, int64_t tok_begin, int64_t tok_count,
-                    int32_t c_begin, int32_t c_count, int32_t n_iter, const int32_t* init_idx,
-                    void* centroids, int32_t* labels, int32_t* sizes, int32_t* offsets,
-                    int32_t* sorted_idx, void* workspace, size_t workspace_bytes, void* stream) {
+int ck_cluster_keys_opt(const ck_shape* sh, const void* K, int64_t tok_begin, int64_t tok_count,
+                        int32_t c_begin, int32_t c_count, int32_t max_iter, uint32_t flags,
+                        const int32_t* init_idx, void* centroids, int32_t* labels, int32_t* sizes,
+                        int32_t* offsets, int32_t* sorted_idx, int32_t* iters_done,
+                        void* workspace, size_t workspace_bytes, void* stream) {
   ck::Dims dm;
   int rc = check_shape(sh, &dm, true);
   if (rc) return rc;
   if ((rc = check_ranges(sh, tok_begin, tok_count, c_begin, c_count))) return rc;
-  if (n_iter < 1) return fail(CK_EINVALID, "n_iter=%d must be at least 1", n_iter);
+  if (max_iter < 1) return fail(CK_EINVALID, "n_iter=%d must be at least 1", max_iter);
+  const int metric = (int)(flags & CK_METRIC_MASK);
+  const bool converge = (flags & CK_KM_UNTIL_CONVERGED) != 0;
+  if (metric > CK_METRIC_IP || (flags & ~(CK_METRIC_MASK | CK_KM_UNTIL_CONVERGED)))
+    return fail(CK_EINVALID, "unknown flags 0x%x", flags);
+  if (converge && max_iter > ck::KM_MAX_ITER_CONVERGE)
+    return fail(CK_EUNSUPPORTED, "at most %d iterations in run-until-convergence mode",
+                ck::KM_MAX_ITER_CONVERGE);
   CK_REQUIRE_PTR(K);
   CK_REQUIRE_PTR(init_idx);
   CK_REQUIRE_PTR(centroids);
@@ -191,6 +200,7 @@ int ck_cluster_keys(const ck_shape* sh, const void* K, int64_t tok_begin, int64_
   CK_REQUIRE_PTR(sizes);
   CK_REQUIRE_PTR(offsets);
   CK_REQUIRE_PTR(sorted_idx);
+  CK_OPTIONAL_PTR(iters_done);
   if (!workspace) return fail(CK_EWORKSPACE, "workspace is NULL");
   if (!aligned16(workspace)) return fail(CK_EMISALIGNED, "workspace is not 16-byte aligned");
   const ck::ClusterWorkspace ws = ck::carve_cluster_workspace(dm, tok_count, c_count, workspace);
@@ -199,21 +209,55 @@ int ck_cluster_keys(const ck_shape* sh, const void* K, int64_t tok_begin, int64_
 
   hipStream_t st = (hipStream_t)stream;
   const ck::bf16* Kb = (const ck::bf16*)K;
+  float* bias = metric == CK_METRIC_L2 ? ws.bias : nullptr;
   hipError_t e = ck::launch_init_centroids(dm, Kb, init_idx, c_begin, c_count,
-                                           (ck::bf16*)centroids, ws.mu_hat, st);
+                                           (ck::bf16*)centroids, ws.mu_hat, metric, bias,
+                                           ws.bias_stride, st);
   if (e != hipSuccess) return hip_result(e, "init launch");
-  for (int it = 0; it < n_iter; ++it) {
+  if (converge) {
+    // one row of changed-label counters per iteration, all zero: a head-problem that
+    // stops leaves its later rows at zero, which is what keeps it stopped
+    e = ck::launch_fill_i32(ws.changed, (int64_t)max_iter * dm.HP, 0, st);
+    if (e != hipSuccess) return hip_result(e, "counter fill launch");
+  }
+  for (int it = 0; it < max_iter; ++it) {
+    ck::KmCtl ctl;
+    ctl.bias = bias;
+    ctl.bias_stride = ws.bias_stride;
+    const int32_t* gate = nullptr;
+    if (converge) {
+      ctl.changed = ws.changed + (int64_t)it * dm.HP;
+      ctl.first = it == 0;
+      ctl.skip = it >= 2 ? ws.changed + (int64_t)(it - 1) * dm.HP : nullptr;
+      gate = it >= 1 ? ctl.changed : nullptr;
+    }
     e = ck::launch_assign(dm, Kb, tok_begin, tok_count, ws.mu_hat, c_begin, c_count, labels,
-                          nullptr, ws.chunk_hist, st);
+                          nullptr, ws.chunk_hist, ctl, st);
     if (e != hipSuccess) return hip_result(e, "assignment launch");
     e = ck::launch_metadata(dm, labels, tok_begin, tok_count, c_begin, c_count, sizes, offsets,
-                            sorted_idx, ws.chunk_hist, true, st);
+                            sorted_idx, ws.chunk_hist, true, gate, st);
     if (e != hipSuccess) return hip_result(e, "metadata launch");
     e = ck::launch_update(dm, Kb, offsets, sorted_idx, c_begin, c_count, (ck::bf16*)centroids,
-                          ws.mu_hat, nullptr, st);
+                          ws.mu_hat, nullptr, metric, bias, ws.bias_stride, gate, st);
     if (e != hipSuccess) return hip_result(e, "update launch");
   }
+  if (iters_done) {
+    if (converge)
+      e = ck::launch_iters_done(ws.changed, max_iter, dm.HP, iters_done, st);
+    else
+      e = ck::launch_fill_i32(iters_done, dm.HP, max_iter, st);
+    if (e != hipSuccess) return hip_result(e, "iteration count launch");
+  }
   return CK_OK;
+}
+
+int ck_cluster_keys(const ck_shape* sh, const void* K, int64_t tok_begin, int64_t tok_count,
+                    int32_t c_begin, int32_t c_count, int32_t n_iter, const int32_t* init_idx,
+                    void* centroids, int32_t* labels, int32_t* sizes, int32_t* offsets,
+                    int32_t* sorted_idx, void* workspace, size_t workspace_bytes, void* stream) {
+  return ck_cluster_keys_opt(sh, K, tok_begin, tok_count, c_begin, c_count, n_iter,
+                             CK_METRIC_COSINE, init_idx, centroids, labels, sizes, offsets,
+                             sorted_idx, nullptr, workspace, workspace_bytes, stream);
 }
 
 int ck_select_clusters(const ck_shape* sh, const void* q, const void* centroids,

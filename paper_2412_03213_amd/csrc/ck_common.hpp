@@ -132,30 +132,51 @@ struct Dims {
 };
 
 
+constexpr int KM_MAX_ITER_CONVERGE = 256;   // iteration cap of the run-until-convergence mode
+
 struct ClusterWorkspace {
-  bf16* mu_hat;       // [HP, c_count, D] unit-length centroids the assignment reads
+  bf16* mu_hat;         // [HP, c_count, D] table the assignment reads (unit-length or raw means)
   int32_t* chunk_hist;  // [HP, n_chunks, c_count] per-chunk histogram / base positions
+  float* bias;          // [HP, bias_stride] -|mu_c|^2 / 2 of the table rows (l2 metric)
+  int bias_stride;      // c_count rounded up to whole 32-row tiles
+  int32_t* changed;     // [KM_MAX_ITER_CONVERGE + 1, HP] labels changed per iteration
   size_t bytes;
+};
+
+// What an assignment launch needs beyond the contraction itself.
+struct KmCtl {
+  const float* bias = nullptr;     // l2 metric: added to <k, mu_c> before the argmax
+  int bias_stride = 0;
+  const int32_t* skip = nullptr;   // [HP] changed-label counts of the previous iteration:
+                                   // 0 = that head-problem has converged, leave it alone
+  int32_t* changed = nullptr;      // [HP] receives the number of labels this launch changed
+  int first = 0;                   // no previous labels exist: count every token as changed
 };
 ClusterWorkspace carve_cluster_workspace(const Dims& dm, int64_t tok_count, int c_count,
                                          void* base);
 
+// metric: CK_METRIC_* of the table the assignment will read
 hipError_t launch_init_centroids(const Dims& dm, const bf16* K, const int32_t* init_idx,
                                  int c_begin, int c_count, bf16* centroids, bf16* mu_hat,
-                                 hipStream_t st);
+                                 int metric, float* bias, int bias_stride, hipStream_t st);
+hipError_t launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t st);
+hipError_t launch_iters_done(const int32_t* changed, int max_iter, int HP, int32_t* iters_done,
+                             hipStream_t st);
 int assign_tile_tokens(const Dims& dm, int64_t tok_count);
 // chunk_hist (nullable): [HP, n_chunks, c_count] label histogram per workgroup tile
 hipError_t launch_assign(const Dims& dm, const bf16* K, int64_t tok_begin, int64_t tok_count,
                          const bf16* mu_hat, int c_begin, int c_count, int32_t* labels,
-                         float* best_sim, int32_t* chunk_hist, hipStream_t st);
+                         float* best_sim, int32_t* chunk_hist, const KmCtl& ctl, hipStream_t st);
 // have_hist: chunk_hist already holds the histograms (written by launch_assign)
 hipError_t launch_metadata(const Dims& dm, const int32_t* labels, int64_t tok_begin,
                            int64_t tok_count, int c_begin, int c_count, int32_t* sizes,
                            int32_t* offsets, int32_t* sorted_idx, int32_t* chunk_hist,
-                           bool have_hist, hipStream_t st);
+                           bool have_hist, const int32_t* gate, hipStream_t st);
+// gate (nullable, [HP]): head-problems whose entry is 0 are left untouched
 hipError_t launch_update(const Dims& dm, const bf16* K, const int32_t* offsets,
                          const int32_t* sorted_idx, int c_begin, int c_count, bf16* centroids,
-                         bf16* mu_hat, float* centroids_f32, hipStream_t st);
+                         bf16* mu_hat, float* centroids_f32, int metric, float* bias,
+                         int bias_stride, const int32_t* gate, hipStream_t st);
 hipError_t launch_select(const Dims& dm, const void* q, const void* centroids,
                          const int32_t* sizes, int n_clusters, int budget, uint32_t flags,
                          int32_t* sel_clusters, int32_t* n_sel_clusters, int32_t* n_sel_tokens,

@@ -24,18 +24,24 @@ constexpr int LDS_ROW = D + 8;             // bf16 elements per LDS row: 272 B, 
 // delay the accumulator read-out of a tile until after the next barrier, so that on
 // every SIMD one wavefront is in its MFMA phase while the other reduces on the
 // vector ALUs.
-template <int NKB, int WAVES, int WAVES_PER_SIMD, bool PHASED>
+// HAS_BIAS (l2 metric): a per-centroid bias, held in LDS, is added to every
+// similarity before the argmax.
+template <int NKB, int WAVES, int WAVES_PER_SIMD, bool PHASED, bool HAS_BIAS>
 __global__ __launch_bounds__(WAVES * 64, WAVES_PER_SIMD) void k_assign(
     const bf16* __restrict__ K, const bf16* __restrict__ mu_hat, int32_t* __restrict__ labels,
     float* __restrict__ best_sim, int32_t* __restrict__ chunk_hist, int n_hist_chunks,
-    int64_t N_cap, int64_t tok_begin, int64_t tok_count, int c_begin, int c_count) {
+    int64_t N_cap, int64_t tok_begin, int64_t tok_count, int c_begin, int c_count,
+    const KmCtl ctl) {
   constexpr int THREADS = WAVES * 64;
   constexpr int SEGS = CHUNK_ROWS * 16 / THREADS;      // 16-byte segments of a chunk per thread
   __shared__ __attribute__((aligned(16))) bf16 lds[2][CHUNK_ROWS * LDS_ROW];
+  __shared__ __attribute__((aligned(16))) float lds_bias[HAS_BIAS ? CK_MAX_CLUSTERS + 32 : 4];
+  __shared__ int s_changed;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 31, half = lane >> 5;
   const int hp = blockIdx.y;
+  if (ctl.skip && ctl.skip[hp] == 0) return;            // converged: whole workgroup leaves
   const bf16* Khp = K + (int64_t)hp * N_cap * D;
   const bf16* Mhp = mu_hat + (int64_t)hp * c_count * D;
 
@@ -62,6 +68,11 @@ __global__ __launch_bounds__(WAVES * 64, WAVES_PER_SIMD) void k_assign(
   };
   // first centroid chunk ahead of the keys, so that it does not queue behind them
   fetch(0);
+  if (tid == 0) s_changed = 0;
+  if constexpr (HAS_BIAS) {
+    for (int c = tid; c < n_tiles * 32; c += THREADS)
+      lds_bias[c] = c < c_count ? ctl.bias[(int64_t)hp * ctl.bias_stride + c] : 0.f;
+  }
 
   // ---- keys of this wavefront into registers, in B-operand layout ----
   // Issued fragment-major (all key blocks' fragment 0, then fragment 1, ...): the first
@@ -117,6 +128,16 @@ __global__ __launch_bounds__(WAVES * 64, WAVES_PER_SIMD) void k_assign(
   auto reduce = [&](int tile_id) {
     const int row0 = tile_id * 32;
     // accumulator i of a lane is centroid row 8*(i/4) + 4*half + i%4 of the tile
+    if constexpr (HAS_BIAS) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const floatx4 b = *reinterpret_cast<const floatx4*>(&lds_bias[row0 + 8 * j + 4 * half]);
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[kb][4 * j + e] += b[e];
+      }
+    }
     if (row0 + 32 > c_count) {                         // wave-uniform: zero-padded rows lose
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
@@ -181,6 +202,7 @@ __global__ __launch_bounds__(WAVES * 64, WAVES_PER_SIMD) void k_assign(
     for (int c = tid; c < HISTS * c_count; c += THREADS) reinterpret_cast<int*>(&lds[0][0])[c] = 0;
     __syncthreads();
   }
+  int diff = 0;
 #pragma unroll
   for (int kb = 0; kb < NKB; ++kb) {
     const int slot = 15 - (int)(__float_as_uint(bestp[kb]) & 15u);
@@ -198,14 +220,20 @@ __global__ __launch_bounds__(WAVES * 64, WAVES_PER_SIMD) void k_assign(
     const int64_t t = wave_tok0 + kb * 32 + col;
     if (half == 0 && t < tok_count) {
       const int64_t o = (int64_t)hp * N_cap + tok_begin + t;
+      if (ctl.changed) diff += (ctl.first || labels[o] != c_begin + bidx) ? 1 : 0;
       labels[o] = c_begin + bidx;
       if (best_sim) best_sim[o] = __uint_as_float(__float_as_uint(best) & 0xFFFFFFF0u);
       if (chunk_hist) atomicAdd(&hist[bidx], 1);       // integer counts: order does not matter
     }
   }
+  if (ctl.changed) {
+    const int wsum = __builtin_amdgcn_readlane(wave_inclusive_scan(diff), WAVE - 1);
+    if (lane == 0 && wsum) atomicAdd(&s_changed, wsum);
+  }
+  if (chunk_hist || ctl.changed) __syncthreads();
+  if (ctl.changed && tid == 0 && s_changed) atomicAdd(&ctl.changed[hp], s_changed);
   // label histograms of this workgroup's tokens = chunks of the counting sort
   if (chunk_hist) {
-    __syncthreads();
     for (int e = tid; e < HISTS * c_count; e += THREADS) {
       const int hc = (int)blockIdx.x * HISTS + e / c_count;
       if (hc < n_hist_chunks)
@@ -219,14 +247,20 @@ template <int NKB, int WAVES, int WPS, bool PHASED>
 static void launch_assign_variant(const Dims& dm, const bf16* K, int64_t tok_begin,
                                   int64_t tok_count, const bf16* mu_hat, int c_begin, int c_count,
                                   int32_t* labels, float* best_sim, int32_t* chunk_hist,
-                                  hipStream_t st) {
+                                  const KmCtl& ctl, hipStream_t st) {
   constexpr int TOK = WAVES * NKB * 32;
   const int sort_chunk = 4 * NKB * 32;
   const int n_hist_chunks = (int)((tok_count + sort_chunk - 1) / sort_chunk);
   dim3 grid((unsigned)((tok_count + TOK - 1) / TOK), dm.HP);
-  hipLaunchKernelGGL((k_assign<NKB, WAVES, WPS, PHASED>), grid, dim3(WAVES * 64), 0, st, K, mu_hat,
-                     labels, best_sim, chunk_hist, n_hist_chunks, dm.N_cap, tok_begin, tok_count,
-                     c_begin, c_count);
+  if (ctl.bias)
+    // the bias table takes 8 KB more LDS: at most three of the small workgroups fit a CU
+    hipLaunchKernelGGL((k_assign<NKB, WAVES, (WPS > 3 ? 3 : WPS), PHASED, true>), grid, dim3(WAVES * 64), 0, st, K,
+                       mu_hat, labels, best_sim, chunk_hist, n_hist_chunks, dm.N_cap, tok_begin,
+                       tok_count, c_begin, c_count, ctl);
+  else
+    hipLaunchKernelGGL((k_assign<NKB, WAVES, WPS, PHASED, false>), grid, dim3(WAVES * 64), 0, st, K,
+                       mu_hat, labels, best_sim, chunk_hist, n_hist_chunks, dm.N_cap, tok_begin,
+                       tok_count, c_begin, c_count, ctl);
 }
 
 // Chunk size of the counting sort = the tokens of four assignment wavefronts (every
@@ -240,13 +274,13 @@ int assign_tile_tokens(const Dims& dm, int64_t tok_count) {
 
 hipError_t launch_assign(const Dims& dm, const bf16* K, int64_t tok_begin, int64_t tok_count,
                          const bf16* mu_hat, int c_begin, int c_count, int32_t* labels,
-                         float* best_sim, int32_t* chunk_hist, hipStream_t st) {
+                         float* best_sim, int32_t* chunk_hist, const KmCtl& ctl, hipStream_t st) {
   if (assign_tile_tokens(dm, tok_count) == 512)
     launch_assign_variant<4, 8, 2, true>(dm, K, tok_begin, tok_count, mu_hat, c_begin, c_count,
-                                         labels, best_sim, chunk_hist, st);
+                                         labels, best_sim, chunk_hist, ctl, st);
   else
     launch_assign_variant<1, 4, 4, false>(dm, K, tok_begin, tok_count, mu_hat, c_begin, c_count,
-                                          labels, best_sim, chunk_hist, st);
+                                          labels, best_sim, chunk_hist, ctl, st);
   return hipGetLastError();
 }
 

@@ -14,10 +14,13 @@
 namespace ck {
 
 // ------------------------------------------------------------------ init
-// centroid c of head-problem hp := key row init_idx[hp][c]; also its unit-length copy.
+// centroid c of head-problem hp := key row init_idx[hp][c]; also the row of the table the
+// assignment reads: its unit-length copy (cosine) or the row itself (l2, inner product),
+// and for l2 the bias -|row|^2 / 2.
 __global__ __launch_bounds__(64) void k_init_centroids(
     const bf16* __restrict__ K, const int32_t* __restrict__ init_idx, int64_t N_cap, int C_cap,
-    int c_begin, int c_count, bf16* __restrict__ centroids, bf16* __restrict__ mu_hat) {
+    int c_begin, int c_count, bf16* __restrict__ centroids, bf16* __restrict__ mu_hat, int metric,
+    float* __restrict__ bias, int bias_stride) {
   const int c = blockIdx.x, hp = blockIdx.y, lane = threadIdx.x;
   int64_t row = init_idx[(int64_t)hp * c_count + c];
   row = row < 0 ? 0 : (row >= N_cap ? N_cap - 1 : row);
@@ -28,14 +31,49 @@ __global__ __launch_bounds__(64) void k_init_centroids(
   reinterpret_cast<uint32_t*>(centroids + ((int64_t)hp * C_cap + c_begin + c) * D)[lane] = w;
   const uint32_t h = (uint32_t)float_to_bf16_bits(a * inv) |
                      ((uint32_t)float_to_bf16_bits(b * inv) << 16);
-  reinterpret_cast<uint32_t*>(mu_hat + ((int64_t)hp * c_count + c) * D)[lane] = h;
+  reinterpret_cast<uint32_t*>(mu_hat + ((int64_t)hp * c_count + c) * D)[lane] =
+      metric == CK_METRIC_COSINE ? h : w;
+  if (metric == CK_METRIC_L2 && lane == 0) bias[(int64_t)hp * bias_stride + c] = -0.5f * n2;
+}
+
+__global__ void k_fill_i32(int32_t* __restrict__ p, int64_t n, int32_t v) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+hipError_t launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t st) {
+  hipLaunchKernelGGL(k_fill_i32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, n, v);
+  return hipGetLastError();
+}
+
+// iterations a head-problem ran: up to and including the first assignment that changed
+// no label, or all of them
+__global__ void k_iters_done(const int32_t* __restrict__ changed, int max_iter, int HP,
+                             int32_t* __restrict__ iters_done) {
+  const int hp = blockIdx.x * blockDim.x + threadIdx.x;
+  if (hp >= HP) return;
+  int n = max_iter;
+  for (int t = 1; t < max_iter; ++t)
+    if (changed[(int64_t)t * HP + hp] == 0) {
+      n = t + 1;
+      break;
+    }
+  iters_done[hp] = n;
+}
+
+hipError_t launch_iters_done(const int32_t* changed, int max_iter, int HP, int32_t* iters_done,
+                             hipStream_t st) {
+  hipLaunchKernelGGL(k_iters_done, dim3((HP + 63) / 64), dim3(64), 0, st, changed, max_iter, HP,
+                     iters_done);
+  return hipGetLastError();
 }
 
 hipError_t launch_init_centroids(const Dims& dm, const bf16* K, const int32_t* init_idx,
                                  int c_begin, int c_count, bf16* centroids, bf16* mu_hat,
-                                 hipStream_t st) {
+                                 int metric, float* bias, int bias_stride, hipStream_t st) {
   hipLaunchKernelGGL(k_init_centroids, dim3(c_count, dm.HP), dim3(64), 0, st, K, init_idx,
-                     dm.N_cap, dm.C_cap, c_begin, c_count, centroids, mu_hat);
+                     dm.N_cap, dm.C_cap, c_begin, c_count, centroids, mu_hat, metric, bias,
+                     bias_stride);
   return hipGetLastError();
 }
 
@@ -89,9 +127,10 @@ constexpr int SCAN_GROUPS = SCAN_THREADS / 64;
 constexpr int SCAN_REG = 16;                            // chunk counts a thread keeps in registers
 __global__ __launch_bounds__(SCAN_THREADS) void k_sort_scan(
     int32_t* __restrict__ chunk_hist, int n_chunks, int C_cap, int c_begin, int c_count,
-    int32_t* __restrict__ sizes) {
+    int32_t* __restrict__ sizes, const int32_t* __restrict__ gate) {
   __shared__ int part[SCAN_GROUPS][64];
   const int cl = threadIdx.x & 63, grp = threadIdx.x >> 6, hp = blockIdx.y;
+  if (gate && gate[hp] == 0) return;
   const int c = blockIdx.x * 64 + cl;
   const int per = (n_chunks + SCAN_GROUPS - 1) / SCAN_GROUPS;
   const int k0 = grp * per, k1 = min(k0 + per, n_chunks);
@@ -140,10 +179,12 @@ __global__ __launch_bounds__(SORT_THREADS) void k_sort_scatter(
     const int32_t* __restrict__ labels, int64_t N_cap, int64_t tok_begin, int64_t tok_count,
     int C_cap, int c_begin, int c_count, int label_bits, int n_chunks, int chunk_tokens,
     const int32_t* __restrict__ chunk_hist, const int32_t* __restrict__ sizes,
-    int32_t* __restrict__ offsets, int32_t* __restrict__ sorted_idx) {
+    int32_t* __restrict__ offsets, int32_t* __restrict__ sorted_idx,
+    const int32_t* __restrict__ gate) {
   extern __shared__ int lds_hist[];                     // [c_count] positions + [4][c_count] counts
   __shared__ int tmp[SORT_THREADS / WAVE + 1];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hp = blockIdx.y;
+  if (gate && gate[hp] == 0) return;
   const int chunk = blockIdx.x;
   int* offs = lds_hist;
   int* cnt = lds_hist + c_count;
@@ -210,7 +251,7 @@ __global__ __launch_bounds__(SORT_THREADS) void k_sort_scatter(
 hipError_t launch_metadata(const Dims& dm, const int32_t* labels, int64_t tok_begin,
                            int64_t tok_count, int c_begin, int c_count, int32_t* sizes,
                            int32_t* offsets, int32_t* sorted_idx, int32_t* chunk_hist,
-                           bool have_hist, hipStream_t st) {
+                           bool have_hist, const int32_t* gate, hipStream_t st) {
   const int chunk_tokens = assign_tile_tokens(dm, tok_count);
   const int n_chunks = (int)((tok_count + chunk_tokens - 1) / chunk_tokens);
   int label_bits = 0;
@@ -221,11 +262,11 @@ hipError_t launch_metadata(const Dims& dm, const int32_t* labels, int64_t tok_be
                        st, labels, dm.N_cap, tok_begin, tok_count, c_begin, c_count, label_bits,
                        n_chunks, chunk_tokens, chunk_hist);
   hipLaunchKernelGGL(k_sort_scan, dim3((c_count + 63) / 64, dm.HP), dim3(SCAN_THREADS), 0, st,
-                     chunk_hist, n_chunks, dm.C_cap, c_begin, c_count, sizes);
+                     chunk_hist, n_chunks, dm.C_cap, c_begin, c_count, sizes, gate);
   hipLaunchKernelGGL(k_sort_scatter, dim3(n_chunks, dm.HP), dim3(SORT_THREADS),
                      (size_t)5 * c_count * sizeof(int), st, labels, dm.N_cap, tok_begin, tok_count,
                      dm.C_cap, c_begin, c_count, label_bits, n_chunks, chunk_tokens, chunk_hist,
-                     sizes, offsets, sorted_idx);
+                     sizes, offsets, sorted_idx, gate);
   return hipGetLastError();
 }
 
@@ -238,9 +279,11 @@ constexpr int UPD_THREADS = 256;
 __global__ __launch_bounds__(UPD_THREADS) void k_update(
     const bf16* __restrict__ K, int64_t N_cap, int C_cap, const int32_t* __restrict__ offsets,
     const int32_t* __restrict__ sorted_idx, int c_begin, int c_count,
-    bf16* __restrict__ centroids, bf16* __restrict__ mu_hat, float* __restrict__ centroids_f32) {
+    bf16* __restrict__ centroids, bf16* __restrict__ mu_hat, float* __restrict__ centroids_f32,
+    int metric, float* __restrict__ bias, int bias_stride, const int32_t* __restrict__ gate) {
   __shared__ float part[4][D];
   const int c = blockIdx.x, hp = blockIdx.y, tid = threadIdx.x;
+  if (gate && gate[hp] == 0) return;
   const int lane = tid & 63, wave = tid >> 6, l16 = tid & 15, grp = tid >> 4;  // 16 groups
   const int32_t* off = offsets + (int64_t)hp * (C_cap + 1) + c_begin + c;
   const int beg = off[0], n = off[1] - beg;
@@ -295,10 +338,19 @@ __global__ __launch_bounds__(UPD_THREADS) void k_update(
     const float inv = n2 > 0.f ? 1.0f / sqrtf(n2) : 0.f;
     const int64_t crow = (int64_t)hp * C_cap + c_begin + c;
     const int64_t hrow = (int64_t)hp * c_count + c;
-    reinterpret_cast<uint32_t*>(centroids + crow * D)[lane] =
+    const uint32_t raw =
         (uint32_t)float_to_bf16_bits(m0) | ((uint32_t)float_to_bf16_bits(m1) << 16);
+    reinterpret_cast<uint32_t*>(centroids + crow * D)[lane] = raw;
+    // table row of the next assignment: unit length (cosine) or the stored mean itself
     reinterpret_cast<uint32_t*>(mu_hat + hrow * D)[lane] =
-        (uint32_t)float_to_bf16_bits(m0 * inv) | ((uint32_t)float_to_bf16_bits(m1 * inv) << 16);
+        metric == CK_METRIC_COSINE
+            ? ((uint32_t)float_to_bf16_bits(m0 * inv) | ((uint32_t)float_to_bf16_bits(m1 * inv) << 16))
+            : raw;
+    if (metric == CK_METRIC_L2) {                       // wave-uniform
+      const float r0 = lo_bf16(raw), r1 = hi_bf16(raw); // the rounded row is what gets compared
+      const float rn2 = wave_sum(r0 * r0 + r1 * r1);
+      if (lane == 0) bias[(int64_t)hp * bias_stride + c] = -0.5f * rn2;
+    }
     if (centroids_f32)
       reinterpret_cast<float2*>(centroids_f32 + hrow * D)[lane] = make_float2(m0, m1);
   }
@@ -306,10 +358,11 @@ __global__ __launch_bounds__(UPD_THREADS) void k_update(
 
 hipError_t launch_update(const Dims& dm, const bf16* K, const int32_t* offsets,
                          const int32_t* sorted_idx, int c_begin, int c_count, bf16* centroids,
-                         bf16* mu_hat, float* centroids_f32, hipStream_t st) {
+                         bf16* mu_hat, float* centroids_f32, int metric, float* bias,
+                         int bias_stride, const int32_t* gate, hipStream_t st) {
   hipLaunchKernelGGL(k_update, dim3(c_count, dm.HP), dim3(UPD_THREADS), 0, st, K, dm.N_cap,
                      dm.C_cap, offsets, sorted_idx, c_begin, c_count, centroids, mu_hat,
-                     centroids_f32);
+                     centroids_f32, metric, bias, bias_stride, gate);
   return hipGetLastError();
 }
 
@@ -322,9 +375,17 @@ ClusterWorkspace carve_cluster_workspace(const Dims& dm, int64_t tok_count, int 
   mu = (mu + 255) & ~(size_t)255;
   size_t hist = (size_t)dm.HP * n_chunks * c_count * sizeof(int32_t);
   hist = (hist + 255) & ~(size_t)255;
-  w.mu_hat = reinterpret_cast<bf16*>(base);
-  w.chunk_hist = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(base) + mu);
-  w.bytes = mu + hist;
+  w.bias_stride = (c_count + 31) / 32 * 32;
+  size_t bias = (size_t)dm.HP * w.bias_stride * sizeof(float);
+  bias = (bias + 255) & ~(size_t)255;
+  size_t chg = (size_t)(KM_MAX_ITER_CONVERGE + 1) * dm.HP * sizeof(int32_t);
+  chg = (chg + 255) & ~(size_t)255;
+  char* b = reinterpret_cast<char*>(base);
+  w.mu_hat = reinterpret_cast<bf16*>(b);
+  w.chunk_hist = reinterpret_cast<int32_t*>(b + mu);
+  w.bias = reinterpret_cast<float*>(b + mu + hist);
+  w.changed = reinterpret_cast<int32_t*>(b + mu + hist + bias);
+  w.bytes = mu + hist + bias + chg;
   return w;
 }
 

@@ -36,6 +36,10 @@ def test_header_constants_match_binding():
     assert int(consts["CK_SEL_WHOLE"]) == ck.CK_SEL_WHOLE
     assert int(consts["CK_SEL_TRIM_LAST"]) == ck.CK_SEL_TRIM_LAST
     assert int(consts["CK_MAX_CLUSTERS"]) == ck.CK_MAX_CLUSTERS
+    assert int(consts["CK_METRIC_COSINE"]) == ck.CK_METRIC_COSINE
+    assert int(consts["CK_METRIC_L2"]) == ck.CK_METRIC_L2
+    assert int(consts["CK_METRIC_IP"]) == ck.CK_METRIC_IP
+    assert int(consts["CK_KM_UNTIL_CONVERGED"]) == ck.CK_KM_UNTIL_CONVERGED
     assert ctypes.sizeof(binding._CkShape) == 32
 
 
@@ -87,6 +91,21 @@ def test_argument_validation_without_a_device():
     expect(-3, cluster, wsb=16)
     expect(-4, cluster, lab=A + 4)
     expect(-1, cluster, sh=ck.Shape(1, 30, 8, 1000, 40))            # Hq not a multiple of Hkv
+
+    def cluster_opt(flags=0, it=10, iters=None, lab=A):
+        s = sh.c()
+        rc = lib.ck_cluster_keys_opt(ctypes.byref(s), A, 0, 1000, 0, 40, it, flags, A, A, lab, A, A,
+                                     A, iters, A, 1 << 30, None)
+        if rc:
+            raise ck.ClusterKVError(rc, lib.ck_strerror(rc).decode(),
+                                    lib.ck_last_error_detail().decode())
+
+    expect(-1, cluster_opt, flags=3)                                # no such metric
+    expect(-1, cluster_opt, flags=8)                                # unknown bit
+    expect(-1, cluster_opt, it=0)
+    expect(-2, cluster_opt, flags=ck.CK_KM_UNTIL_CONVERGED, it=257)
+    expect(-4, cluster_opt, iters=A + 4)
+    expect(-4, cluster_opt, flags=ck.CK_METRIC_L2 | ck.CK_KM_UNTIL_CONVERGED, lab=A + 8)
 
     expect(-1, ck.ck_select_clusters, sh, A, A, A, 0, 10, 0, A, A, A, A)
     expect(-1, ck.ck_select_clusters, sh, A, A, A, 41, 10, 0, A, A, A, A)

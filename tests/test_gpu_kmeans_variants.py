@@ -1,0 +1,132 @@
+"""GPU parity of ck_cluster_keys_opt against the oracle's K-means variants: l2 and
+inner-product assignment (the metrics paper Section V-B compares) and the
+run-until-convergence loop of Section III-B.  Trajectories are compared label by
+label; once the oracle reports a near tie (gap below 1e-4) at some iteration of a
+head-problem, later iterations of that head-problem are only checked for their
+invariants, because one flipped label legitimately changes everything after it."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2412_03213_amd as ck
+from ck_synth import Config, MixtureWorkload, sample_init_indices
+from oracle import clusterkv_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+NEAR_TIE = 1e-4
+METRICS = {O.COSINE: ck.CK_METRIC_COSINE, O.L2: ck.CK_METRIC_L2, O.INNER: ck.CK_METRIC_IP}
+
+
+def np64(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def run_gpu(w, cfg, init, max_iter, flags, want_iters=False):
+    sh = ck.Shape(cfg.S, cfg.Hq, cfg.Hkv, cfg.N, cfg.C)
+    st = ck.ClusterState(sh, DEV, budget=cfg.B)
+    iters = torch.full((cfg.S, cfg.Hkv), -1, dtype=torch.int32, device=DEV) if want_iters else None
+    st.cluster(w.K, init.to(DEV), 0, cfg.N, cfg.C, max_iter, flags=flags, iters_done=iters)
+    torch.cuda.synchronize()
+    return st, iters
+
+
+def check_state(st, cfg, s, h, keys, labels):
+    """Invariants that hold whatever the trajectory: metadata consistent with the labels,
+    every stored centroid the (bf16-rounded) mean of its members."""
+    lab = st.labels[s, h].cpu().numpy()
+    sizes = st.sizes[s, h, :cfg.C].cpu().numpy()
+    offs = st.offsets[s, h, :cfg.C + 1].cpu().numpy()
+    sidx = st.sorted_idx[s, h].cpu().numpy()
+    ws, wo, wi = O.build_metadata(lab, cfg.C)
+    assert sizes.tolist() == ws.tolist() and offs.tolist() == wo.tolist()
+    assert sidx.tolist() == wi.tolist()
+    mu = np64(st.centroids[s, h, :cfg.C])
+    for c in range(cfg.C):
+        if sizes[c]:
+            want = keys[lab == c].mean(axis=0)
+            assert np.allclose(mu[c], want, rtol=2 ** -7, atol=1e-3)
+
+
+@pytest.mark.parametrize("metric", [O.L2, O.INNER, O.COSINE])
+@pytest.mark.parametrize("N,C,M,hq", [(2048 + 37, 50, 64, 2), (3000, 400, 512, 2), (640, 4, 8, 8)])
+def test_metric_trajectory_matches_oracle(metric, N, C, M, hq):
+    cfg = Config(f"v{N}", 1, 1, 2, hq, 128, N, M, C, 10, 256, 11)
+    w = MixtureWorkload(cfg, device=DEV)
+    init = sample_init_indices(w.K, C, cfg.seed)
+    clean = {h: True for h in range(cfg.Hkv)}
+    compared = 0
+    for n_iter in (1, 2, 4):
+        st, _ = run_gpu(w, cfg, init, n_iter, METRICS[metric])
+        for h in range(cfg.Hkv):
+            keys = np64(w.K[0, h])
+            mu, labels, sizes, n_done, tr = O.kmeans_run(keys, init[0, h].numpy(), n_iter, "bf16",
+                                                         metric)
+            got = st.labels[0, h].cpu().numpy()
+            tie_now = tr.gap[-1] < NEAR_TIE
+            tie_before = any((g < NEAR_TIE).any() for g in tr.gap[:-1])
+            if not tie_before:
+                bad = (got != labels) & ~tie_now
+                assert not bad.any(), f"{metric} head {h} iter {n_iter}: {bad.sum()} mismatches"
+                compared += 1
+                if not tie_now.any():
+                    assert st.sizes[0, h, :C].cpu().numpy().tolist() == sizes.tolist()
+                    assert np.allclose(np64(st.centroids[0, h, :C]), mu, rtol=2 ** -7, atol=1e-3)
+            else:
+                clean[h] = False
+            check_state(st, cfg, 0, h, keys, labels)
+    assert compared >= 2          # at least the first iterations are compared everywhere
+
+
+@pytest.mark.parametrize("metric", [O.COSINE, O.L2, O.INNER])
+def test_run_until_convergence(metric):
+    """Low-noise mixture: the loop stops long before the cap, each head-problem on its own
+    count, in the state a longer fixed-count run also reaches."""
+    cfg = Config("conv", 1, 2, 2, 4, 128, 1500, 12, 12, 10, 256, 21)
+    w = MixtureWorkload(cfg, device=DEV)
+    init = sample_init_indices(w.K, cfg.C, cfg.seed)
+    flags = METRICS[metric] | ck.CK_KM_UNTIL_CONVERGED
+    st, iters = run_gpu(w, cfg, init, 60, flags, want_iters=True)
+    it = iters.cpu().numpy()
+    st_long, _ = run_gpu(w, cfg, init, 60, METRICS[metric])
+    for s in range(cfg.S):
+        for h in range(cfg.Hkv):
+            keys = np64(w.K[s, h])
+            mu, labels, sizes, n_done, tr = O.kmeans_run(keys, init[s, h].numpy(), 60, "bf16",
+                                                         metric, until_converged=True)
+            ties = any((g < NEAR_TIE).any() for g in tr.gap)
+            assert 2 <= it[s, h] <= 60
+            if not ties:
+                assert it[s, h] == n_done
+                assert st.labels[s, h].cpu().numpy().tolist() == labels.tolist()
+                assert st.sizes[s, h, :cfg.C].cpu().numpy().tolist() == sizes.tolist()
+            check_state(st, cfg, s, h, keys, labels)
+            if it[s, h] < 60:
+                # a stopped head-problem is at a fixed point: the longer fixed run agrees
+                assert torch.equal(st.labels[s, h], st_long.labels[s, h])
+                assert torch.equal(st.centroids[s, h], st_long.centroids[s, h])
+                assert torch.equal(st.sorted_idx[s, h], st_long.sorted_idx[s, h])
+
+
+def test_fixed_count_reports_all_iterations_and_flags_zero_is_the_default():
+    cfg = Config("dflt", 1, 1, 2, 2, 128, 2048, 64, 32, 10, 256, 0)
+    w = MixtureWorkload(cfg, device=DEV)
+    init = sample_init_indices(w.K, cfg.C, cfg.seed)
+    st, iters = run_gpu(w, cfg, init, 5, 0, want_iters=True)
+    assert iters.cpu().numpy().tolist() == [[5, 5]]
+    sh = ck.Shape(cfg.S, cfg.Hq, cfg.Hkv, cfg.N, cfg.C)
+    st2 = ck.ClusterState(sh, DEV, budget=cfg.B)
+    ck.ck_cluster_keys(sh, w.K, 0, cfg.N, 0, cfg.C, 5, init.to(DEV), st2.centroids, st2.labels,
+                       st2.sizes, st2.offsets, st2.sorted_idx)
+    assert torch.equal(st.labels, st2.labels) and torch.equal(st.centroids, st2.centroids)
+
+
+def test_cap_reached_without_convergence_reports_the_cap():
+    cfg = Config("cap", 1, 1, 2, 2, 128, 4000, 512, 200, 10, 256, 5)
+    w = MixtureWorkload(cfg, device=DEV)
+    init = sample_init_indices(w.K, cfg.C, cfg.seed)
+    st, iters = run_gpu(w, cfg, init, 2, ck.CK_KM_UNTIL_CONVERGED, want_iters=True)
+    st_fix, _ = run_gpu(w, cfg, init, 2, 0)
+    assert iters.cpu().numpy().tolist() == [[2, 2]]
+    assert torch.equal(st.labels, st_fix.labels) and torch.equal(st.centroids, st_fix.centroids)
