@@ -326,6 +326,7 @@ def main():
         "note": "ck_full_decode_attn over all N tokens of the same layer (split-KV + merge)"}
     if not args.no_recall:
         result["recall_rate"] = recall_curves(cfg, w, st, sh)
+        result["kmeans_variants"] = kmeans_variants(cfg, w, init_d, reps)
     result["measured_peaks"] = measured_peaks(dev)
     if not args.no_batch8:
         result["decode_batch8_B2048"] = big_decode(reps, layers=1)
@@ -348,7 +349,7 @@ def main():
     print(json.dumps(result))
 
 
-def recall_curves(cfg, w, st, sh, n_queries=8, page_size=16):
+def recall_curves(cfg, w, st, sh, n_queries=8, page_size=16, budgets=None, with_pages=True):
     """Recall rate |I_T & I_true| / B against the exact top-B tokens (by summed q.k of the
     group), averaged over head-problems and queries, for budgets 256..2048: the cluster
     selection of the clustered state `st` in both budget modes, and the page-granular
@@ -357,7 +358,7 @@ def recall_curves(cfg, w, st, sh, n_queries=8, page_size=16):
     import paper_2412_03213_amd as ck
     dev = w.K.device
     HP, N = cfg.S * cfg.Hkv, cfg.N
-    budgets = list(range(256, 2049, 256))
+    budgets = budgets or list(range(256, 2049, 256))
     n_pages = (N + page_size - 1) // page_size
     pk = torch.empty(cfg.S, cfg.Hkv, n_pages, cfg.d, dtype=w.K.dtype, device=dev)
     ck.ck_page_keys(sh, w.K, 0, N, page_size, pk)
@@ -374,6 +375,8 @@ def recall_curves(cfg, w, st, sh, n_queries=8, page_size=16):
     hits = torch.empty(HP, dtype=torch.int32, device=dev)
     acc = {"clusterkv_trim_last": [0.0] * len(budgets), "clusterkv_whole": [0.0] * len(budgets),
            f"page{page_size}": [0.0] * len(budgets)}
+    if not with_pages:
+        del acc[f"page{page_size}"]
     for _ in range(n_queries):
         q = w.query()
         ck.ck_token_scores(sh, q, w.K, 0, N, tscore)
@@ -389,6 +392,8 @@ def recall_curves(cfg, w, st, sh, n_queries=8, page_size=16):
                 ck.ck_gather_indices(sh, sel, nsel, st.offsets, st.sorted_idx, B, mode, tok, ntok)
                 ck.ck_recall_hits(HP, tok, ntok, ref, nref, hits)
                 acc[name][bi] += float(hits.sum()) / (HP * B)
+            if not with_pages:
+                continue
             pidx = torch.empty(HP, B // page_size, dtype=torch.int32, device=dev)
             ck.ck_topk_select(HP, pscore, n_pages, 0, n_pages, B // page_size, pidx, npg)
             ck.ck_expand_pages(HP, pidx, npg, page_size, 0, N, tok, ntok)
@@ -399,6 +404,45 @@ def recall_curves(cfg, w, st, sh, n_queries=8, page_size=16):
                    "trim_last recalls exactly B tokens, whole clusters at most B"}
     for k, v in acc.items():
         out[k] = [round(x / n_queries, 4) for x in v]
+    return out
+
+
+def kmeans_variants(cfg, w, init_d, reps):
+    """The clustering options beside the default: assignment metric (time of the fixed
+    10-iteration run and recall at the configured budget) and the run-until-convergence
+    loop (iterations each head-problem took, time of the whole call)."""
+    import torch
+    import paper_2412_03213_amd as ck
+    dev = w.K.device
+    sh = ck.Shape(cfg.S, cfg.Hq, cfg.Hkv, cfg.N, cfg.C)
+    out = {}
+    for name, flag in (("cosine", ck.CK_METRIC_COSINE), ("l2", ck.CK_METRIC_L2),
+                       ("inner_product", ck.CK_METRIC_IP)):
+        st = ck.ClusterState(sh, dev, budget=cfg.B)
+
+        def cluster():
+            st.n_clusters = 0
+            st.cluster(w.K, init_d, 0, cfg.N, cfg.C, cfg.n_iter, flags=flag)
+
+        cluster()
+        ms = event_ms(cluster, max(3, reps // 4))
+        rc = recall_curves(cfg, w, st, sh, n_queries=4, budgets=[cfg.B], with_pages=False)
+        out[name] = {"kmeans_ms": ms, f"recall_at_B{cfg.B}_trim_last": rc["clusterkv_trim_last"][0]}
+    st = ck.ClusterState(sh, dev, budget=cfg.B)
+    iters = torch.zeros(cfg.S, cfg.Hkv, dtype=torch.int32, device=dev)
+    cap = 100
+
+    def converge():
+        st.n_clusters = 0
+        st.cluster(w.K, init_d, 0, cfg.N, cfg.C, cap, flags=ck.CK_KM_UNTIL_CONVERGED,
+                   iters_done=iters)
+
+    converge()
+    ms = event_ms(converge, 3)
+    it = iters.flatten().cpu().tolist()
+    out["until_converged_cosine"] = {"cap": cap, "iterations_min": min(it),
+                                     "iterations_mean": sum(it) / len(it),
+                                     "iterations_max": max(it), "kmeans_ms": ms}
     return out
 
 
