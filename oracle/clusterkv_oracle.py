@@ -453,3 +453,33 @@ def page_select(q_group, keys, page_size, budget, tok_begin=0, tok_count=None):
     s = token_scores(q_group, rep)
     pages = topk_indices(s, budget // page_size)
     return pages, expand_pages(pages, page_size, n, tok_begin)
+
+
+# --------------------------------------------------------------------------
+# cluster-granularity cache of recalled K/V (Section IV-D), R = 1
+# --------------------------------------------------------------------------
+def cache_step(held_clusters, selected_clusters, sizes):
+    """One decode step against a cache that holds the clusters recalled at the
+    previous step: a selected cluster found there is a hit, every other one is
+    loaded from the home copy.  Returns (hit_tokens, miss_tokens, new_held):
+    token counts of both kinds and the cluster list the cache holds afterwards
+    (exactly this step's selection, in its order)."""
+    held = set(int(c) for c in held_clusters)
+    hit = miss = 0
+    for c in selected_clusters:
+        if int(c) in held:
+            hit += int(sizes[int(c)])
+        else:
+            miss += int(sizes[int(c)])
+    return hit, miss, [int(c) for c in selected_clusters]
+
+
+def cache_hit_rate(selections, sizes):
+    """Token-weighted hit rate of a sequence of per-step selections (whole
+    clusters), starting from an empty cache."""
+    held, hit_t, all_t = [], 0, 0
+    for sel in selections:
+        h, m, held = cache_step(held, sel, sizes)
+        hit_t += h
+        all_t += h + m
+    return hit_t / all_t if all_t else 0.0
