@@ -65,12 +65,20 @@ class MixtureWorkload:
         v = torch.randn(n, d, generator=g, device=self.device)
         return k.to(self.dtype), v.to(self.dtype), tc
 
-    def query(self) -> torch.Tensor:
+    def query(self, sticky: float = 0.0) -> torch.Tensor:
         """One decode-step query, [S, Hq, d]; heads of one group draw centers
-        of their own KV head independently."""
+        of their own KV head independently.  With sticky > 0 a head keeps the
+        center of its previous query with that probability (a stand-in for the
+        slow drift of attention targets between consecutive decode steps)."""
         cfg = self.cfg
         S, Hq, G, d, M = cfg.S, cfg.Hq, cfg.G, cfg.d, cfg.M
         pick = torch.randint(0, M, (S, Hq), generator=self._g_q, device=self.device)
+        if sticky > 0.0:
+            keep = torch.rand(S, Hq, generator=self._g_q, device=self.device) < sticky
+            last = getattr(self, "_last_pick", None)
+            if last is not None:
+                pick = torch.where(keep, last, pick)
+            self._last_pick = pick
         kv_head = torch.arange(Hq, device=self.device) // G
         c = self.centers[torch.arange(S, device=self.device)[:, None], kv_head[None, :], pick]
         q = _SCALE * c + _SIGMA * torch.randn(S, Hq, d, generator=self._g_q,

@@ -346,6 +346,73 @@ int ck_expand_pages(int32_t n_problems, const int32_t* page_idx, const int32_t* 
                     int64_t tok_count, int32_t* token_idx, int32_t idx_stride,
                     int32_t* n_tokens, void* stream);
 
+/* ------------------------------------------------------------------------
+ * Cluster-granularity cache of recalled K/V over a home copy in host memory
+ * (paper Section IV-A: K/V are offloaded after prefill and only selected tokens
+ * are loaded back; Section IV-D: a cache on the GPU keeps the K/V of the clusters
+ * selected at the last R steps, so that only clusters not present are loaded).
+ * R = 1 here, the value the paper settles on.
+ * ---------------------------------------------------------------------- */
+
+/*
+ * Device buffers of the cache, all allocated by the caller.  Two generations
+ * alternate: a step reads generation (step_parity ^ 1) and writes generation
+ * step_parity.
+ *   K[g], V[g]   [S, Hkv, cap_tokens, d] in sh->dtype: rows of the recalled list of a
+ *                step, in recalled order.
+ *   clusters[g]  int32 [S, Hkv, C_cap]: ids of the clusters held, in buffer order.
+ *   starts[g]    int32 [S, Hkv, C_cap + 1]: first row of each held cluster; the entry
+ *                after the last one is the number of rows in use.
+ *   n_held[g]    int32 [S, Hkv].
+ *   cap_tokens   rows per head-problem; must be >= the budget of every step.
+ */
+typedef struct ck_cluster_cache {
+  void* K[2];
+  void* V[2];
+  int32_t* clusters[2];
+  int32_t* starts[2];
+  int32_t* n_held[2];
+  int32_t cap_tokens;
+  int32_t reserved;
+} ck_cluster_cache;
+
+/*
+ * Device-visible address of pinned host memory (hipHostMalloc, or a torch tensor
+ * created with pin_memory=True): *dev_ptr [host out].  Errors: CK_EINVALID for NULL,
+ * CK_EHIP if the runtime does not know the address as mapped pinned memory.
+ */
+int ck_host_device_ptr(void* host_ptr, void** dev_ptr);
+
+/* Empties both generations (n_held := 0).  Enqueues one small kernel. */
+int ck_cache_reset(const ck_shape* sh, const ck_cluster_cache* cache, void* stream);
+
+/*
+ * One decode step with the cache: selection as ck_select_clusters (whole clusters
+ * only: a cached cluster is always complete), then every selected cluster is copied
+ * into generation step_parity of the cache, from generation step_parity ^ 1 if it is
+ * held there, else row by row from the home copy through sorted_idx; then attention
+ * over exactly those rows.  out equals what ck_decode_step computes on K/V resident in
+ * device memory, bit for bit.
+ *   K_home, V_home  device-visible pointers to K/V [S, Hkv, N_cap, d]: pinned host
+ *                   memory (ck_host_device_ptr) or device memory.  Read by the GPU
+ *                   itself; rows of missing clusters only.
+ *   miss_tokens     [dev] int32 [S, Hkv] out: rows loaded from the home copy this step
+ *                   (n_sel_tokens - miss_tokens were found in the cache).
+ *   sinks and a recent window are not supported here (the step attends the recalled
+ *   list only).
+ *   workspace: ck_workspace_bytes(sh, CK_WS_SPARSE_ATTN, budget, 0).
+ * Calls on one cache must be ordered on one stream; step_parity alternates 0, 1, 0, ...
+ * Errors: CK_EINVALID (null, n_clusters / budget out of range, budget > cap_tokens,
+ *   step_parity not 0 or 1), CK_EUNSUPPORTED, CK_EWORKSPACE, CK_EMISALIGNED, CK_EHIP.
+ */
+int ck_cached_decode_step(const ck_shape* sh, const void* q, const void* K_home,
+                          const void* V_home, const void* centroids, const int32_t* sizes,
+                          const int32_t* offsets, const int32_t* sorted_idx, int32_t n_clusters,
+                          int32_t budget, const ck_cluster_cache* cache, int32_t step_parity,
+                          float softmax_scale, float* scores, int32_t* sel_clusters,
+                          int32_t* n_sel_clusters, int32_t* n_sel_tokens, int32_t* miss_tokens,
+                          void* out, void* workspace, size_t workspace_bytes, void* stream);
+
 /*
  * Measurement aid, not part of the method: a register-only loop of
  * v_mfma_f32_32x32x16_bf16 (the instruction the assignment step of Section III-B

@@ -8,7 +8,8 @@ PyTorch fallback: a missing library is an error.
 """
 from .binding import (CK_BF16, CK_F32, CK_KM_UNTIL_CONVERGED, CK_METRIC_COSINE, CK_METRIC_IP,
                       CK_METRIC_L2, CK_SEL_TRIM_LAST, CK_SEL_WHOLE, CK_MAX_CLUSTERS,
-                      ClusterKVError, ClusterState, Shape, ck_build_metadata, ck_cluster_keys,
+                      ClusterCache, ClusterKVError, ClusterState, Shape, cached_decode_step,
+                      ck_cache_reset, ck_cached_decode_step, ck_host_device_ptr, ck_build_metadata, ck_cluster_keys,
                       ck_cluster_keys_opt,
                       ck_decode_step, ck_expand_pages, ck_full_decode_attn, ck_gather_indices,
                       ck_kmeans_assign, ck_kmeans_update, ck_page_keys, ck_probe_mfma_bf16,
@@ -18,7 +19,8 @@ from .binding import (CK_BF16, CK_F32, CK_KM_UNTIL_CONVERGED, CK_METRIC_COSINE, 
 __all__ = [
     "CK_BF16", "CK_F32", "CK_KM_UNTIL_CONVERGED", "CK_METRIC_COSINE", "CK_METRIC_IP",
     "CK_METRIC_L2", "CK_SEL_TRIM_LAST", "CK_SEL_WHOLE", "CK_MAX_CLUSTERS", "ck_cluster_keys_opt",
-    "ClusterKVError", "ClusterState", "Shape", "ck_build_metadata", "ck_cluster_keys",
+    "ClusterCache", "ClusterKVError", "ClusterState", "Shape", "cached_decode_step",
+    "ck_cache_reset", "ck_cached_decode_step", "ck_host_device_ptr", "ck_build_metadata", "ck_cluster_keys",
     "ck_decode_step", "ck_expand_pages", "ck_full_decode_attn", "ck_gather_indices",
     "ck_kmeans_assign", "ck_kmeans_update", "ck_page_keys", "ck_probe_mfma_bf16",
     "ck_recall_hits", "ck_select_clusters", "ck_sparse_decode_attn", "ck_token_scores",

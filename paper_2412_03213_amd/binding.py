@@ -25,7 +25,8 @@ EXPORTS = ("ck_version", "ck_strerror", "ck_last_error_detail", "ck_workspace_by
            "ck_cluster_keys", "ck_cluster_keys_opt", "ck_kmeans_assign", "ck_build_metadata", "ck_kmeans_update",
            "ck_select_clusters", "ck_gather_indices", "ck_sparse_decode_attn", "ck_decode_step",
            "ck_full_decode_attn", "ck_token_scores", "ck_topk_select", "ck_recall_hits",
-           "ck_page_keys", "ck_expand_pages", "ck_probe_mfma_bf16")
+           "ck_page_keys", "ck_expand_pages", "ck_host_device_ptr", "ck_cache_reset",
+           "ck_cached_decode_step", "ck_probe_mfma_bf16")
 
 
 class ClusterKVError(RuntimeError):
@@ -38,6 +39,13 @@ class _CkShape(ctypes.Structure):
     _fields_ = [("S", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
                 ("d", ctypes.c_int32), ("N_cap", ctypes.c_int64), ("C_cap", ctypes.c_int32),
                 ("dtype", ctypes.c_int32)]
+
+
+class _CkClusterCache(ctypes.Structure):
+    _fields_ = [("K", ctypes.c_void_p * 2), ("V", ctypes.c_void_p * 2),
+                ("clusters", ctypes.c_void_p * 2), ("starts", ctypes.c_void_p * 2),
+                ("n_held", ctypes.c_void_p * 2), ("cap_tokens", ctypes.c_int32),
+                ("reserved", ctypes.c_int32)]
 
 
 @dataclass(frozen=True)
@@ -116,6 +124,14 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.ck_page_keys.argtypes = [SH, P, I64, I64, I32, P, I64, P]
     lib.ck_expand_pages.restype = ctypes.c_int
     lib.ck_expand_pages.argtypes = [I32, P, P, I32, I32, I64, I64, P, I32, P, P]
+    CC = ctypes.POINTER(_CkClusterCache)
+    lib.ck_host_device_ptr.restype = ctypes.c_int
+    lib.ck_host_device_ptr.argtypes = [P, ctypes.POINTER(ctypes.c_void_p)]
+    lib.ck_cache_reset.restype = ctypes.c_int
+    lib.ck_cache_reset.argtypes = [SH, CC, P]
+    lib.ck_cached_decode_step.restype = ctypes.c_int
+    lib.ck_cached_decode_step.argtypes = [SH, P, P, P, P, P, P, P, I32, I32, CC, I32, F, P, P, P,
+                                          P, P, P, P, SZ, P]
     lib.ck_probe_mfma_bf16.restype = ctypes.c_int
     lib.ck_probe_mfma_bf16.argtypes = [I32, I32, P, ctypes.POINTER(ctypes.c_double), P]
     _lib = lib
@@ -312,6 +328,87 @@ def ck_expand_pages(n_problems, page_idx, n_pages, page_size, tok_begin, tok_cou
     _check(lib.ck_expand_pages(n_problems, _ptr(page_idx), _ptr(n_pages), pstride, page_size,
                                tok_begin, tok_count, _ptr(token_idx), istride, _ptr(n_tokens),
                                _stream(page_idx)))
+
+
+def ck_host_device_ptr(host) -> int:
+    """Device-visible address of a pinned host tensor (or of a raw pinned address)."""
+    lib = load_library()
+    out = ctypes.c_void_p(0)
+    addr = host if isinstance(host, int) else host.data_ptr()
+    _check(lib.ck_host_device_ptr(addr, ctypes.byref(out)))
+    return out.value
+
+
+class ClusterCache:
+    """Device buffers of the cluster-granularity cache (two generations) for one layer."""
+
+    def __init__(self, sh: Shape, device, cap_tokens: int):
+        self.sh, self.cap = sh, cap_tokens
+        dt = sh.torch_dtype
+        self.K = [torch.zeros(sh.S, sh.Hkv, cap_tokens, sh.d, dtype=dt, device=device)
+                  for _ in range(2)]
+        self.V = [torch.zeros(sh.S, sh.Hkv, cap_tokens, sh.d, dtype=dt, device=device)
+                  for _ in range(2)]
+        self.clusters = [torch.zeros(sh.S, sh.Hkv, sh.C_cap, dtype=torch.int32, device=device)
+                         for _ in range(2)]
+        self.starts = [torch.zeros(sh.S, sh.Hkv, sh.C_cap + 1, dtype=torch.int32, device=device)
+                       for _ in range(2)]
+        self.n_held = [torch.zeros(sh.S, sh.Hkv, dtype=torch.int32, device=device)
+                       for _ in range(2)]
+        self.miss_tokens = torch.zeros(sh.S, sh.Hkv, dtype=torch.int32, device=device)
+        self.step = 0
+
+    def c(self) -> _CkClusterCache:
+        two = ctypes.c_void_p * 2
+        return _CkClusterCache(two(*[_ptr(t) for t in self.K]), two(*[_ptr(t) for t in self.V]),
+                               two(*[_ptr(t) for t in self.clusters]),
+                               two(*[_ptr(t) for t in self.starts]),
+                               two(*[_ptr(t) for t in self.n_held]), self.cap, 0)
+
+
+def ck_cache_reset(sh: Shape, cache):
+    lib = load_library()
+    s = sh.c()
+    c = cache.c() if isinstance(cache, ClusterCache) else cache
+    _check(lib.ck_cache_reset(ctypes.byref(s), ctypes.byref(c) if c is not None else None,
+                              _stream(cache.K[0]) if isinstance(cache, ClusterCache) else 0))
+    if isinstance(cache, ClusterCache):
+        cache.step = 0
+
+
+def ck_cached_decode_step(sh: Shape, q, K_home, V_home, centroids, sizes, offsets, sorted_idx,
+                          n_clusters, budget, cache, step_parity, scores, sel_clusters,
+                          n_sel_clusters, n_sel_tokens, miss_tokens, out, softmax_scale=None,
+                          workspace=None):
+    """K_home / V_home: device tensors, or device-visible addresses (int) of pinned host
+    memory as returned by ck_host_device_ptr."""
+    lib = load_library()
+    if softmax_scale is None:
+        softmax_scale = sh.d ** -0.5
+    if workspace is None:
+        workspace = _workspace(ck_workspace_bytes(sh, CK_WS_SPARSE_ATTN, budget), q)
+    s = sh.c()
+    c = cache.c() if isinstance(cache, ClusterCache) else cache
+    _check(lib.ck_cached_decode_step(ctypes.byref(s), _ptr(q), _ptr(K_home), _ptr(V_home),
+                                     _ptr(centroids), _ptr(sizes), _ptr(offsets),
+                                     _ptr(sorted_idx), n_clusters, budget,
+                                     ctypes.byref(c) if c is not None else None, step_parity,
+                                     softmax_scale, _ptr(scores), _ptr(sel_clusters),
+                                     _ptr(n_sel_clusters), _ptr(n_sel_tokens), _ptr(miss_tokens),
+                                     _ptr(out), _ptr(workspace),
+                                     workspace.numel() if isinstance(workspace, torch.Tensor)
+                                     else 0, _stream(q)))
+    return workspace
+
+
+def cached_decode_step(st, cache: ClusterCache, q, K_home, V_home):
+    """One cached decode step on the clustered state `st`; alternates the generations."""
+    ck_cached_decode_step(st.sh, q, K_home, V_home, st.centroids, st.sizes, st.offsets,
+                          st.sorted_idx, st.n_clusters, st.budget, cache, cache.step & 1,
+                          st.scores, st.sel_clusters, st.n_sel_clusters, st.n_sel_tokens,
+                          cache.miss_tokens, st.out, workspace=st.attn_ws)
+    cache.step += 1
+    return st.out
 
 
 def ck_probe_mfma_bf16(n_workgroups: int, iters: int, sink) -> float:

@@ -19,7 +19,8 @@ OBJ_DIR = os.path.join(ROOT, "_build")
 LIB = os.path.join(PKG, "libclusterkv.so")
 
 SOURCES = ["api.hip", "kmeans_assign.hip", "kmeans_update.hip", "select_gather.hip",
-           "sparse_attn.hip", "evaluate.hip", "probe.hip"]
+           "sparse_attn.hip", "evaluate.hip", "cluster_cache.hip",
+           "probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed-FP32 instruction selection is kept off for every device function

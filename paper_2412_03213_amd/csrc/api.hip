@@ -528,6 +528,123 @@ int ck_expand_pages(int32_t n_problems, const int32_t* page_idx, const int32_t* 
                     "page expansion launch");
 }
 
+int ck_host_device_ptr(void* host_ptr, void** dev_ptr) {
+  if (!host_ptr || !dev_ptr) return fail(CK_EINVALID, "host_ptr or dev_ptr is NULL");
+  void* d = nullptr;
+  const hipError_t e = hipHostGetDevicePointer(&d, host_ptr, 0);
+  if (e != hipSuccess || !d) {
+    (void)hipGetLastError();
+    return fail(CK_EHIP, "not mapped pinned host memory: %s", hipGetErrorString(e));
+  }
+  *dev_ptr = d;
+  return CK_OK;
+}
+
+namespace {
+int check_cache(const ck_shape* sh, const ck_cluster_cache* cache) {
+  if (!cache) return fail(CK_EINVALID, "cache is NULL");
+  if (cache->cap_tokens < 1) return fail(CK_EINVALID, "cap_tokens=%d must be positive", cache->cap_tokens);
+  for (int g = 0; g < 2; ++g) {
+    CK_REQUIRE_PTR(cache->K[g]);
+    CK_REQUIRE_PTR(cache->V[g]);
+    CK_REQUIRE_PTR(cache->clusters[g]);
+    CK_REQUIRE_PTR(cache->starts[g]);
+    CK_REQUIRE_PTR(cache->n_held[g]);
+  }
+  (void)sh;
+  return CK_OK;
+}
+}  // namespace
+
+int ck_cache_reset(const ck_shape* sh, const ck_cluster_cache* cache, void* stream) {
+  ck::Dims dm;
+  int rc = check_shape(sh, &dm, false);
+  if (rc) return rc;
+  if ((rc = check_cache(sh, cache))) return rc;
+  for (int g = 0; g < 2; ++g) {
+    const hipError_t e = ck::launch_fill_i32(cache->n_held[g], dm.HP, 0, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_result(e, "cache reset launch");
+  }
+  return CK_OK;
+}
+
+int ck_cached_decode_step(const ck_shape* sh, const void* q, const void* K_home,
+                          const void* V_home, const void* centroids, const int32_t* sizes,
+                          const int32_t* offsets, const int32_t* sorted_idx, int32_t n_clusters,
+                          int32_t budget, const ck_cluster_cache* cache, int32_t step_parity,
+                          float softmax_scale, float* scores, int32_t* sel_clusters,
+                          int32_t* n_sel_clusters, int32_t* n_sel_tokens, int32_t* miss_tokens,
+                          void* out, void* workspace, size_t workspace_bytes, void* stream) {
+  ck::Dims dm;
+  int rc = check_shape(sh, &dm, false);
+  if (rc) return rc;
+  if (n_clusters < 1 || n_clusters > sh->C_cap)
+    return fail(CK_EINVALID, "n_clusters=%d outside [1, C_cap=%d]", n_clusters, sh->C_cap);
+  if (n_clusters > CK_MAX_CLUSTERS)
+    return fail(CK_EUNSUPPORTED, "%d clusters (at most %d)", n_clusters, CK_MAX_CLUSTERS);
+  if (budget < 1) return fail(CK_EINVALID, "budget=%d must be positive", budget);
+  if (step_parity != 0 && step_parity != 1)
+    return fail(CK_EINVALID, "step_parity=%d must be 0 or 1", step_parity);
+  if ((rc = check_cache(sh, cache))) return rc;
+  if (budget > cache->cap_tokens)
+    return fail(CK_EINVALID, "budget=%d exceeds the cache's %d rows", budget, cache->cap_tokens);
+  if (!(softmax_scale > 0.f)) return fail(CK_EINVALID, "softmax_scale must be positive");
+  CK_REQUIRE_PTR(q);
+  CK_REQUIRE_PTR(K_home);
+  CK_REQUIRE_PTR(V_home);
+  CK_REQUIRE_PTR(centroids);
+  CK_REQUIRE_PTR(sizes);
+  CK_REQUIRE_PTR(offsets);
+  CK_REQUIRE_PTR(sorted_idx);
+  CK_REQUIRE_PTR(scores);
+  CK_REQUIRE_PTR(sel_clusters);
+  CK_REQUIRE_PTR(n_sel_clusters);
+  CK_REQUIRE_PTR(n_sel_tokens);
+  CK_REQUIRE_PTR(miss_tokens);
+  CK_REQUIRE_PTR(out);
+  ck::Dims dc = dm;                                     // the cache buffers as the K/V of attention
+  dc.N_cap = cache->cap_tokens;
+  const size_t need = ck::attn_workspace_bytes(dm, budget);
+  if (!workspace) return fail(CK_EWORKSPACE, "workspace is NULL");
+  if (!aligned16(workspace)) return fail(CK_EMISALIGNED, "workspace is not 16-byte aligned");
+  if (workspace_bytes < need)
+    return fail(CK_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+  hipStream_t st = (hipStream_t)stream;
+  hipError_t e = ck::launch_select(dm, q, centroids, sizes, n_clusters, budget, CK_SEL_WHOLE,
+                                   sel_clusters, n_sel_clusters, n_sel_tokens, scores, st);
+  if (e != hipSuccess) return hip_result(e, "selection launch");
+  const int g = step_parity, o = step_parity ^ 1;
+  ck::CacheArgs a;
+  a.K_home = K_home;
+  a.V_home = V_home;
+  a.K_old = cache->K[o];
+  a.V_old = cache->V[o];
+  a.K_new = cache->K[g];
+  a.V_new = cache->V[g];
+  a.old_clusters = cache->clusters[o];
+  a.old_starts = cache->starts[o];
+  a.old_n = cache->n_held[o];
+  a.new_clusters = cache->clusters[g];
+  a.new_starts = cache->starts[g];
+  a.new_n = cache->n_held[g];
+  a.sel_clusters = sel_clusters;
+  a.n_sel_clusters = n_sel_clusters;
+  a.sizes = sizes;
+  a.offsets = offsets;
+  a.sorted_idx = sorted_idx;
+  a.miss_tokens = miss_tokens;
+  a.N_cap = dm.N_cap;
+  a.C_cap = dm.C_cap;
+  a.cap = cache->cap_tokens;
+  a.row_bytes = dm.dtype == CK_BF16 ? 256 : 512;
+  e = ck::launch_cache_fill(dm, a, budget, st);
+  if (e != hipSuccess) return hip_result(e, "cache fill launch");
+  // attention over the first n_sel_tokens rows of the new generation
+  return hip_result(ck::launch_sparse_attn(dc, q, cache->K[g], cache->V[g], nullptr, n_sel_tokens,
+                                           0, budget, 0, 0, 0, softmax_scale, out, workspace, st),
+                    "attention launch");
+}
+
 int ck_probe_mfma_bf16(int32_t n_workgroups, int32_t iters, float* sink, double* flops,
                        void* stream) {
   if (n_workgroups < 1 || n_workgroups > 65535 || iters < 1 || iters > (1 << 24))

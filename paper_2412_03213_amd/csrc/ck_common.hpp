@@ -196,6 +196,20 @@ hipError_t launch_gather(const Dims& dm, const int32_t* sel_clusters,
                          const int32_t* sorted_idx, int budget, uint32_t flags,
                          int32_t* token_idx, int idx_stride, int32_t* n_tokens, hipStream_t st);
 hipError_t launch_probe_mfma(int n_workgroups, int iters, float* sink, hipStream_t st);
+// cluster cache
+struct CacheArgs {
+  const void *K_home, *V_home;                          // [HP, N_cap, D]
+  const void *K_old, *V_old;                            // [HP, cap, D] rows of the previous step
+  void *K_new, *V_new;
+  const int32_t *old_clusters, *old_starts, *old_n;     // [HP, C_cap], [HP, C_cap + 1], [HP]
+  int32_t *new_clusters, *new_starts, *new_n;
+  const int32_t *sel_clusters, *n_sel_clusters;         // this step's selection (score order)
+  const int32_t *sizes, *offsets, *sorted_idx;
+  int32_t* miss_tokens;                                 // [HP] rows fetched from the home copy
+  int64_t N_cap;
+  int C_cap, cap, row_bytes;
+};
+hipError_t launch_cache_fill(const Dims& dm, const CacheArgs& a, int budget, hipStream_t st);
 // evaluation helpers
 hipError_t launch_row_scores(const Dims& dm, const void* q, const void* table,
                              int64_t table_stride, int64_t row_begin, int n_rows, float* scores,

@@ -153,7 +153,8 @@ __global__ __launch_bounds__(ATT_THREADS) void k_attn_partial(const AttnArgs a) 
         row = a.sorted_idx[(int64_t)hp * a.N_cap + src];
         a.token_idx_out[(int64_t)hp * a.idx_stride + qpos] = (int32_t)row;
       } else {
-        row = a.token_idx[(int64_t)hp * a.idx_stride + qpos];
+        // no list: the first n_tokens rows of K/V themselves (a dense per-head-problem prefix)
+        row = a.token_idx ? a.token_idx[(int64_t)hp * a.idx_stride + qpos] : qpos;
       }
     } else {
       row = a.recent_begin + (p - a.n_sink - n_idx);

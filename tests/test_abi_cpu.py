@@ -182,6 +182,29 @@ def test_argument_validation_without_a_device():
     expect(-1, ck.ck_expand_pages, 8, A, A, 0, 0, 1000, A, A)
     expect(-1, ck.ck_expand_pages, 8, A, None, 16, 0, 1000, A, A)
 
+    # cluster cache
+    two = ctypes.c_void_p * 2
+
+    def cache_struct(cap=64, K0=A):
+        return binding._CkClusterCache(two(K0, A), two(A, A), two(A, A), two(A, A), two(A, A),
+                                       cap, 0)
+
+    def cached(cache=None, B=16, parity=0, miss=A, nc=40, ws=A):
+        ck.ck_cached_decode_step(sh, A, A, A, A, A, A, A, nc, B,
+                                 cache_struct() if cache is None else cache, parity, A, A, A, A,
+                                 miss, A, workspace=ws)
+
+    expect(-1, cached, B=65)                                        # budget above the cache rows
+    expect(-1, cached, parity=2)
+    expect(-1, cached, miss=None)
+    expect(-1, cached, nc=41)
+    expect(-1, cached, cache=cache_struct(cap=0))
+    expect(-1, cached, cache=cache_struct(K0=None))
+    expect(-4, cached, cache=cache_struct(K0=A + 4))
+    expect(-3, cached, ws=0)
+    expect(-1, ck.ck_cache_reset, sh, cache_struct(cap=0))
+    expect(-1, ck.ck_host_device_ptr, 0)
+
 
 def test_missing_library_is_an_error(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_lib", None)
