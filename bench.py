@@ -42,6 +42,9 @@ def parse():
                     help="skip the recall-rate curves (cluster vs page selection vs exact top-B)")
     ap.add_argument("--no-offload", action="store_true",
                     help="skip the host-resident K/V leg (cluster cache over pinned host memory)")
+    ap.add_argument("--no-stack", action="store_true",
+                    help="skip the 32-layer driver leg (side-stream clustering, sinks, full-KV "
+                         "first layers)")
     ap.add_argument("--full-depth", action="store_true",
                     help="also run all 32 layers x 8 sequences of the full-depth configuration "
                          "as one batch of 2048 head-problems (needs ~36 GiB of HBM)")
@@ -329,6 +332,8 @@ def main():
     if not args.no_recall:
         result["recall_rate"] = recall_curves(cfg, w, st, sh)
         result["kmeans_variants"] = kmeans_variants(cfg, w, init_d, reps)
+    if not args.no_stack:
+        result["layer_stack_32"] = layer_stack(cfg, w, init_d)
     if not args.no_offload:
         result["offloaded_kv_cluster_cache"] = [offloaded_kv(cfg, w, st, sh, sticky=p)
                                                 for p in (0.8, 0.95)]
@@ -499,6 +504,75 @@ def offloaded_kv(cfg, w, st, sh, steps=64, sticky=0.8):
             "host_link_GBps_uncached": miss_n * row / len(qs) / (ms_n * 1e-3) / 1e9,
             "note": "the hit rate is a property of the synthetic query stream, not of real "
                     "attention; times include two small bookkeeping adds per step"}
+
+
+def layer_stack(cfg, w, init_d, n_layers=32):
+    """The paper's serving arrangement on one sequence: 32 layers, 16 attention sinks, the
+    first two layers on the full KV cache, prefill clustering of every layer on a side
+    stream while a stand-in for the layer's dense work (one [N x 4096] x [4096 x 14336] bf16
+    GEMM) runs on the main stream.  All layers share one synthetic K/V (same shapes, same
+    work; only the memory is saved)."""
+    import torch
+    import paper_2412_03213_amd as ck
+    dev = w.K.device
+    stack = ck.LayerStack(n_layers, cfg.S, cfg.Hq, cfg.Hkv, cfg.N, 0, cfg.C, cfg.B, dev,
+                          n_sink=16, full_kv_layers=2, n_iter=cfg.n_iter)
+    sink_init = init_d.clamp(min=16)
+    x = torch.randn(cfg.N, 4096, device=dev, dtype=torch.bfloat16)
+    wt = torch.randn(4096, 14336, device=dev, dtype=torch.bfloat16)
+    y = torch.empty(cfg.N, 14336, device=dev, dtype=torch.bfloat16)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(fn, reps=3):
+        fn()
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(reps):
+            fn()
+        torch.cuda.current_stream().wait_stream(stack.side)
+        b.record()
+        b.synchronize()
+        return a.elapsed_time(b) / reps
+
+    def dense_only():
+        for _ in range(n_layers):
+            torch.matmul(x, wt, out=y)
+
+    def overlapped():
+        for l in range(n_layers):
+            torch.matmul(x, wt, out=y)
+            stack.cluster_prefill(l, w.K, sink_init)
+
+    def serial():
+        for l in range(n_layers):
+            torch.matmul(x, wt, out=y)
+            if stack.compressed(l):
+                st = stack.states[l]
+                st.n_clusters = 0
+                st.cluster(w.K, sink_init, 16, cfg.N - 16, cfg.C, cfg.n_iter)
+
+    t_dense, t_over, t_serial = timed(dense_only), timed(overlapped), timed(serial)
+    q = w.query()
+
+    def decode_policy():
+        for l in range(n_layers):
+            stack.decode(l, q, w.K, w.V, cfg.N)
+
+    def decode_full():
+        for l in range(n_layers):
+            ck.ck_full_decode_attn(stack.sh, q, w.K, w.V, cfg.N, stack.full_out,
+                                   workspace=stack.full_ws)
+
+    d_pol, d_full = timed(decode_policy, 20), timed(decode_full, 20)
+    return {"workload": f"{n_layers} layers x {cfg.name}, 16 sinks, first 2 layers full KV",
+            "prefill_dense_standin_ms": t_dense,
+            "prefill_with_clustering_on_side_stream_ms": t_over,
+            "prefill_with_clustering_in_line_ms": t_serial,
+            "clustering_overhead_hidden_frac":
+                1.0 - (t_over - t_dense) / max(t_serial - t_dense, 1e-9),
+            "decode_attention_us_per_token_policy": d_pol * 1e3,
+            "decode_attention_us_per_token_full_kv": d_full * 1e3,
+            "decode_attention_speedup": d_full / d_pol}
 
 
 def long_context(reps):

@@ -15,8 +15,10 @@ from .binding import (CK_BF16, CK_F32, CK_KM_UNTIL_CONVERGED, CK_METRIC_COSINE, 
                       ck_kmeans_assign, ck_kmeans_update, ck_page_keys, ck_probe_mfma_bf16,
                       ck_recall_hits, ck_select_clusters, ck_sparse_decode_attn, ck_token_scores,
                       ck_topk_select, ck_version, ck_workspace_bytes, decode_step, load_library)
+from .driver import LayerStack
 
 __all__ = [
+    "LayerStack",
     "CK_BF16", "CK_F32", "CK_KM_UNTIL_CONVERGED", "CK_METRIC_COSINE", "CK_METRIC_IP",
     "CK_METRIC_L2", "CK_SEL_TRIM_LAST", "CK_SEL_WHOLE", "CK_MAX_CLUSTERS", "ck_cluster_keys_opt",
     "ClusterCache", "ClusterKVError", "ClusterState", "Shape", "cached_decode_step",
