@@ -42,9 +42,11 @@ def parse():
                     help="skip the recall-rate curves (cluster vs page selection vs exact top-B)")
     ap.add_argument("--no-offload", action="store_true",
                     help="skip the host-resident K/V leg (cluster cache over pinned host memory)")
-    ap.add_argument("--no-stack", action="store_true",
-                    help="skip the 32-layer driver leg (side-stream clustering, sinks, full-KV "
-                         "first layers)")
+    ap.add_argument("--extras", action="store_true",
+                    help="also run the clustering-variants leg (metrics, run-until-convergence) "
+                         "and the 32-layer driver leg (side-stream clustering, sinks, full-KV "
+                         "first layers); off by default so that the default run's kernel trace "
+                         "holds only launches of the timed workloads")
     ap.add_argument("--full-depth", action="store_true",
                     help="also run all 32 layers x 8 sequences of the full-depth configuration "
                          "as one batch of 2048 head-problems (needs ~36 GiB of HBM)")
@@ -331,8 +333,9 @@ def main():
         "note": "ck_full_decode_attn over all N tokens of the same layer (split-KV + merge)"}
     if not args.no_recall:
         result["recall_rate"] = recall_curves(cfg, w, st, sh)
+    if args.extras:
         result["kmeans_variants"] = kmeans_variants(cfg, w, init_d, reps)
-    if not args.no_stack:
+    if args.extras:
         result["layer_stack_32"] = layer_stack(cfg, w, init_d)
     if not args.no_offload:
         result["offloaded_kv_cluster_cache"] = [offloaded_kv(cfg, w, st, sh, sticky=p)
