@@ -18,7 +18,7 @@ INCLUDE = os.path.join(ROOT, "include")
 OBJ_DIR = os.path.join(ROOT, "_build")
 LIB = os.path.join(PKG, "libclusterkv.so")
 
-SOURCES = ["api.hip", "kmeans_assign.hip", "kmeans_update.hip", "select_gather.hip",
+SOURCES = ["api.hip", "kmeans_assign.hip", "kmeans_update.hip", "kmeans_small.hip", "select_gather.hip",
            "sparse_attn.hip", "evaluate.hip", "cluster_cache.hip",
            "probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

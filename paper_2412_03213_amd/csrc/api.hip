@@ -209,6 +209,12 @@ int ck_cluster_keys_opt(const ck_shape* sh, const void* K, int64_t tok_begin, in
 
   hipStream_t st = (hipStream_t)stream;
   const ck::bf16* Kb = (const ck::bf16*)K;
+  if (ck::kmeans_small_fits(tok_count, c_count))        // a few hundred tokens: one launch does it all
+    return hip_result(ck::launch_kmeans_small(dm, Kb, tok_begin, tok_count, c_begin, c_count,
+                                              max_iter, metric, converge, init_idx,
+                                              (ck::bf16*)centroids, labels, sizes, offsets,
+                                              sorted_idx, iters_done, st),
+                      "small K-means launch");
   float* bias = metric == CK_METRIC_L2 ? ws.bias : nullptr;
   hipError_t e = ck::launch_init_centroids(dm, Kb, init_idx, c_begin, c_count,
                                            (ck::bf16*)centroids, ws.mu_hat, metric, bias,

@@ -132,6 +132,8 @@ struct Dims {
 };
 
 
+constexpr int KM_SMALL_MAX_TOKENS = 384;    // token ranges up to this size (and up to
+constexpr int KM_SMALL_MAX_CLUSTERS = 8;    // this many clusters) are clustered by one kernel
 constexpr int KM_MAX_ITER_CONVERGE = 256;   // iteration cap of the run-until-convergence mode
 
 struct ClusterWorkspace {
@@ -160,6 +162,12 @@ hipError_t launch_init_centroids(const Dims& dm, const bf16* K, const int32_t* i
                                  int c_begin, int c_count, bf16* centroids, bf16* mu_hat,
                                  int metric, float* bias, int bias_stride, hipStream_t st);
 hipError_t launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t st);
+bool kmeans_small_fits(int64_t tok_count, int c_count);
+hipError_t launch_kmeans_small(const Dims& dm, const bf16* K, int64_t tok_begin, int64_t tok_count,
+                               int c_begin, int c_count, int max_iter, int metric, bool converge,
+                               const int32_t* init_idx, bf16* centroids, int32_t* labels,
+                               int32_t* sizes, int32_t* offsets, int32_t* sorted_idx,
+                               int32_t* iters_done, hipStream_t st);
 hipError_t launch_iters_done(const int32_t* changed, int max_iter, int HP, int32_t* iters_done,
                              hipStream_t st);
 int assign_tile_tokens(const Dims& dm, int64_t tok_count);

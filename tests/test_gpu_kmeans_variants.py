@@ -50,7 +50,8 @@ def check_state(st, cfg, s, h, keys, labels):
 
 
 @pytest.mark.parametrize("metric", [O.L2, O.INNER, O.COSINE])
-@pytest.mark.parametrize("N,C,M,hq", [(2048 + 37, 50, 64, 2), (3000, 400, 512, 2), (640, 4, 8, 8)])
+@pytest.mark.parametrize("N,C,M,hq", [(2048 + 37, 50, 64, 2), (3000, 400, 512, 2), (640, 4, 8, 8),
+                                      (320, 4, 8, 8), (384, 8, 16, 2), (97, 3, 4, 4)])
 def test_metric_trajectory_matches_oracle(metric, N, C, M, hq):
     cfg = Config(f"v{N}", 1, 1, 2, hq, 128, N, M, C, 10, 256, 11)
     w = MixtureWorkload(cfg, device=DEV)
@@ -107,6 +108,42 @@ def test_run_until_convergence(metric):
                 assert torch.equal(st.labels[s, h], st_long.labels[s, h])
                 assert torch.equal(st.centroids[s, h], st_long.centroids[s, h])
                 assert torch.equal(st.sorted_idx[s, h], st_long.sorted_idx[s, h])
+
+
+@pytest.mark.parametrize("metric", [O.COSINE, O.L2, O.INNER])
+def test_run_until_convergence_small_range(metric):
+    """The single-kernel path for a few hundred tokens: same stopping rule, appended after
+    existing clusters and tokens."""
+    N0, m, C0, cp = 1000, 320, 10, 4
+    cfg = Config("convs", 1, 2, 2, 4, 128, N0 + m, 6, C0 + cp, 10, 256, 33)
+    w = MixtureWorkload(cfg, device=DEV)
+    sh = ck.Shape(cfg.S, cfg.Hq, cfg.Hkv, cfg.N, cfg.C)
+    st = ck.ClusterState(sh, DEV, budget=cfg.B)
+    st.cluster(w.K, sample_init_indices(w.K, C0, 1, 0, N0).to(DEV), 0, N0, C0, 3)
+    init = sample_init_indices(w.K, cp, 2, N0, m)
+    iters = torch.full((cfg.S, cfg.Hkv), -1, dtype=torch.int32, device=DEV)
+    st.cluster(w.K, init.to(DEV), N0, m, cp, 40, flags=METRICS[metric] | ck.CK_KM_UNTIL_CONVERGED,
+               iters_done=iters)
+    torch.cuda.synchronize()
+    it = iters.cpu().numpy()
+    for s in range(cfg.S):
+        for h in range(cfg.Hkv):
+            keys = np64(w.K[s, h])
+            mu, labels, sizes, n_done, tr = O.kmeans_run(keys[N0:], init[s, h].numpy() - N0, 40,
+                                                         "bf16", metric, until_converged=True)
+            ties = any((g < NEAR_TIE).any() for g in tr.gap)
+            got = st.labels[s, h, N0:].cpu().numpy() - C0
+            assert got.min() >= 0 and got.max() < cp
+            if not ties:
+                assert it[s, h] == n_done
+                assert got.tolist() == labels.tolist()
+                assert st.sizes[s, h, C0:].cpu().numpy().tolist() == sizes.tolist()
+                assert np.allclose(np64(st.centroids[s, h, C0:]), mu, rtol=2 ** -7, atol=1e-3)
+            lab_all = st.labels[s, h].cpu().numpy()
+            ws_, wo, wi = O.build_metadata(lab_all, cfg.C)
+            assert st.sizes[s, h].cpu().numpy().tolist() == ws_.tolist()
+            assert st.offsets[s, h].cpu().numpy().tolist() == wo.tolist()
+            assert st.sorted_idx[s, h].cpu().numpy().tolist() == wi.tolist()
 
 
 def test_fixed_count_reports_all_iterations_and_flags_zero_is_the_default():
