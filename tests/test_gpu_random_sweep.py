@@ -1,0 +1,79 @@
+"""Randomised sweep of the whole path on small shapes: random batch, head counts, GQA group,
+context, cluster count, budget, sinks, recent window and budget mode.  Every case checks
+the clustering invariants, fused == three-call decode (bit for bit) and the decode step
+against the oracle on the GPU's own tables (index lists exact off near-ties, attention
+within tolerance)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2412_03213_amd as ck
+from ck_synth import Config, MixtureWorkload, sample_init_indices
+from oracle import clusterkv_oracle as O
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def np64(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shape(seed):
+    rng = np.random.default_rng(1000 + seed)
+    S = int(rng.integers(1, 3))
+    Hkv = int(rng.integers(1, 4))
+    G = int(rng.choice([1, 2, 4, 8]))
+    N = int(rng.integers(40, 3000))
+    n_sink = int(rng.choice([0, 0, 5, 16]))
+    n_recent = int(rng.choice([0, 0, 7, 33]))
+    n_clu_tok = N - n_sink - n_recent
+    C = int(rng.integers(1, min(n_clu_tok, 300) + 1))
+    B = int(rng.integers(1, n_clu_tok + 50))
+    mode = int(rng.choice([ck.CK_SEL_WHOLE, ck.CK_SEL_TRIM_LAST]))
+    n_iter = int(rng.integers(1, 5))
+    cfg = Config(f"r{seed}", 1, S, Hkv, Hkv * G, 128, N, max(2, C // 2), C, n_iter, B, seed)
+    w = MixtureWorkload(cfg, device=DEV)
+    sh = ck.Shape(S, Hkv * G, Hkv, N, C)
+    st = ck.ClusterState(sh, DEV, budget=B, max_recent=n_recent, n_sink=n_sink)
+    init = sample_init_indices(w.K, C, seed, n_sink, n_clu_tok)
+    st.cluster(w.K, init.to(DEV), n_sink, n_clu_tok, C, n_iter)
+    q = w.query()
+    rb, re = N - n_recent, N
+    out_f = ck.decode_step(st, q, w.K, w.V, flags=mode, n_sink=n_sink, recent_begin=rb,
+                           recent_end=re, fused=True).clone()
+    idx_f, n_f = st.token_idx.clone(), st.n_tokens.clone()
+    out_3 = ck.decode_step(st, q, w.K, w.V, flags=mode, n_sink=n_sink, recent_begin=rb,
+                           recent_end=re, fused=False).clone()
+    torch.cuda.synchronize()
+    assert torch.equal(out_f, out_3)
+    assert torch.equal(n_f, st.n_tokens)
+    for s in range(S):
+        for h in range(Hkv):
+            n = int(n_f[s, h])
+            assert torch.equal(idx_f[s, h, :n], st.token_idx[s, h, :n])
+            keys, vals = np64(w.K[s, h]), np64(w.V[s, h])
+            lab = st.labels[s, h, n_sink:n_sink + n_clu_tok].cpu().numpy()
+            sizes, offs, sidx = O.build_metadata(lab, C, tok_begin=n_sink)
+            assert st.sizes[s, h].cpu().numpy().tolist() == sizes.tolist()
+            assert st.offsets[s, h].cpu().numpy().tolist() == offs.tolist()
+            assert st.sorted_idx[s, h, :n_clu_tok].cpu().numpy().tolist() == sidx.tolist()
+            mu = np64(st.centroids[s, h])
+            for c in range(C):
+                if sizes[c]:
+                    want = keys[n_sink:n_sink + n_clu_tok][lab == c].mean(axis=0)
+                    assert np.allclose(mu[c], want, rtol=2 ** -7, atol=2e-3)
+            qg = np64(q[s, h * G:(h + 1) * G])
+            r = O.decode_step(qg, keys, vals, mu, sizes, offs, sidx, B, mode, n_sink, rb, re)
+            got_idx = idx_f[s, h, :n].cpu().numpy()
+            if not O.selection_near_tie(r["scores"], r["order"], r["n_sel"]):
+                assert got_idx.tolist() == r["idx"].tolist()
+            assert n <= B and (mode == ck.CK_SEL_WHOLE or n == min(B, n_clu_tok))
+            want = O.sparse_attention(qg, keys, vals, got_idx, n_sink, rb, re)
+            got = np64(out_f[s, h * G:(h + 1) * G])
+            if len(got_idx) + n_sink + n_recent == 0:
+                assert (got == 0).all()
+            else:
+                err = (np.abs(got - want).max(axis=-1) / np.abs(want).max(axis=-1)).max()
+                assert err <= 2e-2, err
