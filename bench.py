@@ -47,9 +47,10 @@ def parse():
                          "and the 32-layer driver leg (side-stream clustering, sinks, full-KV "
                          "first layers); off by default so that the default run's kernel trace "
                          "holds only launches of the timed workloads")
-    ap.add_argument("--full-depth", action="store_true",
-                    help="also run all 32 layers x 8 sequences of the full-depth configuration "
-                         "as one batch of 2048 head-problems (needs ~36 GiB of HBM)")
+    ap.add_argument("--no-full-depth", action="store_true",
+                    help="skip the full-depth configuration (all 32 layers x 8 sequences as one "
+                         "batch of 2048 head-problems, ~36 GiB of HBM): the decode workload "
+                         "on which the HBM roofline fraction is meaningful")
     return ap.parse_args()
 
 
@@ -349,7 +350,7 @@ def main():
         result["incremental_decode_b16"] = incremental_decode()
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, w, init, q)
-    if args.full_depth:
+    if not args.no_full_depth:
         del w, st
         torch.cuda.empty_cache()
         result["decode_full_depth_32layers"] = big_decode(max(reps // 2, 5), layers=32)
