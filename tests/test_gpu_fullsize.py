@@ -96,6 +96,38 @@ def test_full_depth_one_layer_sampled():
     assert np.all((nt > 0) & (nt <= cfg.B))
 
 
+def test_full_depth_all_layers_as_one_batch_sampled():
+    """All 32 layers x 8 sequences as ONE batch of 2048 head-problems, the launch shape of
+    bench.py's full-depth leg (32 GiB of K+V): sampled head-problems against the oracle,
+    structure of every head-problem."""
+    c2 = get_config(2)
+    cfg = Config("full_depth_32_layers", 1, c2.S * c2.layers, c2.Hkv, c2.Hq, c2.d, c2.N, c2.M,
+                 c2.C, c2.n_iter, c2.B, c2.seed)
+    assert cfg.S * cfg.Hkv == 2048
+    w = MixtureWorkload(cfg, device=DEV)
+    w.token_center = None
+    init = sample_init_indices(w.K, cfg.C, cfg.seed)
+    sh = ck.Shape(cfg.S, cfg.Hq, cfg.Hkv, cfg.N, cfg.C)
+    st = ck.ClusterState(sh, DEV, budget=cfg.B)
+    st.cluster(w.K, init.to(DEV), 0, cfg.N, cfg.C, cfg.n_iter)
+    q = w.query()
+    out = ck.decode_step(st, q, w.K, w.V)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(22)
+    near = 0
+    for s, h in [(0, 0), (255, 7), (100, 3), (31, 6), (200, 1)]:
+        near += check_head_problem(cfg, w, st, q, out, s, h, rng)
+    sizes = st.sizes.cpu().numpy()
+    assert np.all(sizes.sum(axis=-1) == cfg.N)
+    offs = st.offsets.cpu().numpy()
+    assert np.all(offs[..., 0] == 0) and np.all(offs[..., -1] == cfg.N)
+    assert np.all(np.diff(offs, axis=-1) == sizes)
+    nt = st.n_tokens.cpu().numpy()
+    assert np.all((nt > 0) & (nt <= cfg.B))
+    assert bool(torch.isfinite(out.float()).all())
+    print(f"full depth as one batch: selection near-ties {near}/5")
+
+
 def test_incremental_decode_full_size_sampled():
     cfg = get_config(4)
     steps, m, cp = cfg.decode_steps, cfg.m_incr, cfg.c_incr
