@@ -3,6 +3,8 @@ context, cluster count, budget, sinks, recent window and budget mode.  Every cas
 the clustering invariants, fused == three-call decode (bit for bit) and the decode step
 against the oracle on the GPU's own tables (index lists exact off near-ties, attention
 within tolerance)."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -19,7 +21,10 @@ def np64(t):
     return t.detach().float().cpu().numpy().astype(np.float64)
 
 
-@pytest.mark.parametrize("seed", range(24))
+N_SEEDS = int(os.environ.get("CK_SWEEP_SEEDS", "24"))     # more seeds for a longer soak
+
+
+@pytest.mark.parametrize("seed", range(N_SEEDS))
 def test_random_shape(seed):
     rng = np.random.default_rng(1000 + seed)
     S = int(rng.integers(1, 3))
