@@ -11,8 +11,6 @@
 
 namespace ck {
 
-constexpr int SM_THREADS = 512;
-constexpr int SM_SLICES = SM_THREADS / WAVE;            // partial sums of the update: one per wavefront
 
 struct SmallArgs {
   const bf16* K;
@@ -23,14 +21,18 @@ struct SmallArgs {
   int tok_count, C_cap, c_begin, c_count, max_iter, metric, converge;
 };
 
+// MAXC: compile-time bound of the cluster count (register arrays); SM_THREADS: workgroup size
+// (more wavefronts hide the LDS and cross-lane latencies of the 16-lane dot products).
+template <int MAXC, int SM_THREADS>
 __global__ __launch_bounds__(SM_THREADS) void k_kmeans_small(const SmallArgs a) {
+  constexpr int SM_SLICES = SM_THREADS / WAVE;           // partial sums of the update: one per wavefront
   __shared__ __attribute__((aligned(16))) bf16 keys[KM_SMALL_MAX_TOKENS * D];
-  __shared__ __attribute__((aligned(16))) float table[KM_SMALL_MAX_CLUSTERS][D];
-  __shared__ float mu[KM_SMALL_MAX_CLUSTERS][D];
-  __shared__ float part[SM_SLICES][KM_SMALL_MAX_CLUSTERS][D];
-  __shared__ int cnt[SM_SLICES][KM_SMALL_MAX_CLUSTERS];
-  __shared__ int wave_cnt[SM_THREADS / WAVE][KM_SMALL_MAX_CLUSTERS];
-  __shared__ float bias[KM_SMALL_MAX_CLUSTERS];
+  __shared__ __attribute__((aligned(16))) float table[MAXC][D];
+  __shared__ float mu[MAXC][D];
+  __shared__ float part[SM_SLICES][MAXC][D];
+  __shared__ int cnt[SM_SLICES][MAXC];
+  __shared__ int wave_cnt[SM_THREADS / WAVE][MAXC];
+  __shared__ float bias[MAXC];
   __shared__ int lab[KM_SMALL_MAX_TOKENS];
   __shared__ int s_changed;
 
@@ -49,8 +51,8 @@ __global__ __launch_bounds__(SM_THREADS) void k_kmeans_small(const SmallArgs a) 
     mu[c][ch] = bf16_bits_to_float(reinterpret_cast<const uint16_t*>(Khp + row * D)[ch]);
   }
   for (int t = tid; t < n_tok; t += SM_THREADS) lab[t] = -1;
-  for (int e = tid; e < SM_SLICES * KM_SMALL_MAX_CLUSTERS; e += SM_THREADS)
-    cnt[e / KM_SMALL_MAX_CLUSTERS][e % KM_SMALL_MAX_CLUSTERS] = 0;
+  for (int e = tid; e < SM_SLICES * MAXC; e += SM_THREADS)
+    cnt[e / MAXC][e % MAXC] = 0;
   __syncthreads();
 
   const int l16 = tid & 15, grp = tid >> 4;             // 32 groups of 16 lanes
@@ -84,10 +86,10 @@ __global__ __launch_bounds__(SM_THREADS) void k_kmeans_small(const SmallArgs a) 
     // ---- assignment, and the sums of the update in the same pass: 16 lanes per key, 8
     // channels per lane; every lane of the group learns the label and adds its channels of
     // the key to the sums of that cluster.  A stopped run discards the sums. ----
-    float tb[KM_SMALL_MAX_CLUSTERS][8], acc[KM_SMALL_MAX_CLUSTERS][8];
-    int n[KM_SMALL_MAX_CLUSTERS];
+    float tb[MAXC][8], acc[MAXC][8];
+    int n[MAXC];
 #pragma unroll
-    for (int c = 0; c < KM_SMALL_MAX_CLUSTERS; ++c) {
+    for (int c = 0; c < MAXC; ++c) {
       n[c] = 0;
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
@@ -104,7 +106,7 @@ __global__ __launch_bounds__(SM_THREADS) void k_kmeans_small(const SmallArgs a) 
       float best = 0.f;
       int bc = 0;
 #pragma unroll
-      for (int c = 0; c < KM_SMALL_MAX_CLUSTERS; ++c) {
+      for (int c = 0; c < MAXC; ++c) {
         if (c < C) {                                    // uniform
           float d = 0.f;
 #pragma unroll
@@ -117,7 +119,7 @@ __global__ __launch_bounds__(SM_THREADS) void k_kmeans_small(const SmallArgs a) 
         }
       }
 #pragma unroll
-      for (int c = 0; c < KM_SMALL_MAX_CLUSTERS; ++c) {
+      for (int c = 0; c < MAXC; ++c) {
         if (c < C) {
           const float on = bc == c ? 1.f : 0.f;
           n[c] += bc == c ? 1 : 0;
@@ -134,7 +136,7 @@ __global__ __launch_bounds__(SM_THREADS) void k_kmeans_small(const SmallArgs a) 
     if (lane == 0 && diff) atomicAdd(&s_changed, diff);
     // the four groups of a wavefront, then (below) the wavefronts in order
 #pragma unroll
-    for (int c = 0; c < KM_SMALL_MAX_CLUSTERS; ++c) {
+    for (int c = 0; c < MAXC; ++c) {
       if (c < C) {
         n[c] += __shfl_xor(n[c], 16, WAVE);
         n[c] += __shfl_xor(n[c], 32, WAVE);
@@ -233,7 +235,10 @@ hipError_t launch_kmeans_small(const Dims& dm, const bf16* K, int64_t tok_begin,
   a.max_iter = max_iter;
   a.metric = metric;
   a.converge = converge ? 1 : 0;
-  hipLaunchKernelGGL(k_kmeans_small, dim3(dm.HP), dim3(SM_THREADS), 0, st, a);
+  if (c_count <= 4)
+    hipLaunchKernelGGL((k_kmeans_small<4, 1024>), dim3(dm.HP), dim3(1024), 0, st, a);
+  else
+    hipLaunchKernelGGL((k_kmeans_small<KM_SMALL_MAX_CLUSTERS, 512>), dim3(dm.HP), dim3(512), 0, st, a);
   return hipGetLastError();
 }
 
