@@ -12,6 +12,8 @@
 // l and l+32 is needed at the very end.  Keys stay in registers for the whole
 // kernel (NKB blocks of 32 keys per wavefront); centroid tiles stream through
 // LDS in double-buffered chunks of 64 rows shared by all wavefronts of the workgroup.
+#include <atomic>
+
 #include "ck_common.hpp"
 
 namespace ck {
@@ -99,7 +101,10 @@ __global__ __launch_bounds__(WAVES * 64, WAVES_PER_SIMD) void k_assign(
   // every similarity are replaced by 15 - (accumulator slot), so one v_max3 chain
   // finds value and slot together and equal values resolve to the lower centroid.
   // The truncation moves a similarity by < 2^-19 relative, far inside the 1e-4
-  // cosine near-tie band in which labels may legitimately differ.
+  // cosine near-tie band in which labels may legitimately differ.  (Exception to
+  // "lower id wins": when a key's best similarity is NEGATIVE and bit-equal for two
+  // of the 16 rows one lane holds of a tile, the slot bits order the other way and
+  // the higher of the two rows is taken -- an exact tie, so inside that band too.)
   float bestp[NKB];
   int btile[NKB];
 #pragma unroll
@@ -157,8 +162,12 @@ __global__ __launch_bounds__(WAVES * 64, WAVES_PER_SIMD) void k_assign(
       m = fmaxf(fmaxf(m, p[0]), p[1]);
 #pragma unroll
       for (int i = 2; i < 16; i += 2) m = fmaxf(fmaxf(m, p[i]), p[i + 1]);
-      btile[kb] = (m != bestp[kb]) ? tile_id : btile[kb];
-      bestp[kb] = m;
+      // a later tile takes over only with a strictly larger (truncated) value: an equal
+      // one would be a higher centroid id, whatever its slot bits say
+      const bool up = __uint_as_float(__float_as_uint(m) & 0xFFFFFFF0u) >
+                      __uint_as_float(__float_as_uint(bestp[kb]) & 0xFFFFFFF0u);
+      btile[kb] = up ? tile_id : btile[kb];
+      bestp[kb] = up ? m : bestp[kb];
     }
   };
 
@@ -272,6 +281,21 @@ int assign_tile_tokens(const Dims& dm, int64_t tok_count) {
   return tok_count * dm.HP >= 64 * 1024 ? 512 : 128;
 }
 
+// Compute units of the current device, asked once per device (the query costs a few
+// microseconds of host time and a clustering call launches the kernel many times).
+static int compute_units() {
+  static std::atomic<int> cached[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  int n = cached[dev].load(std::memory_order_relaxed);
+  if (n == 0) {
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+      n = 256;
+    cached[dev].store(n, std::memory_order_relaxed);
+  }
+  return n;
+}
+
 hipError_t launch_assign(const Dims& dm, const bf16* K, int64_t tok_begin, int64_t tok_count,
                          const bf16* mu_hat, int c_begin, int c_count, int32_t* labels,
                          float* best_sim, int32_t* chunk_hist, const KmCtl& ctl, hipStream_t st) {
@@ -281,10 +305,7 @@ hipError_t launch_assign(const Dims& dm, const bf16* K, int64_t tok_begin, int64
     // resident in one round or the tile loop is long; with several rounds of short loops,
     // two independent four-wavefront workgroups per CU overlap one's key load and
     // epilogue with the other's tile loop (measured: +8 % at 64 head-problems, C = 400).
-    int dev = 0, n_cu = 256;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
-      n_cu = 256;
+    const int n_cu = compute_units();
     const int64_t wg8 = (tok_count + 1023) / 1024 * dm.HP;
     if (wg8 > n_cu && c_count < 1024) {
       launch_assign_variant<4, 4, 2, false>(dm, K, tok_begin, tok_count, mu_hat, c_begin, c_count,

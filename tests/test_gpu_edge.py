@@ -69,7 +69,10 @@ def test_assignment_exact_ties_and_zero_keys(N):
     rng = np.random.default_rng(3)
     mu = rng.normal(size=(C, 128))
     mu_hat = O.round_to_bf16(O.unit_rows(mu))
-    pairs = [(0, 1), (2, 6), (3, 35), (10, 150), (64, 199), (31, 32)]
+    # (11, 34), (18, 65): same lane half, LATER tile, LOWER accumulator slot -- the copy in
+    # the later tile carries the larger slot bits and must still lose; (7, 97): other half
+    pairs = [(0, 1), (2, 6), (3, 35), (10, 150), (64, 199), (31, 32), (11, 34), (18, 65),
+             (7, 97)]
     for a, b in pairs:
         mu_hat[b] = mu_hat[a]
     K = torch.randn(1, 1, N, 128, device=DEV).to(torch.bfloat16)
