@@ -13,7 +13,9 @@
  * ------------------------------------
  *  - Pointers marked [dev] are device (HBM) pointers, [host] are host pointers.
  *    All device buffers are allocated, owned and freed by the caller; the
- *    library allocates no device memory and keeps no state between calls.
+ *    library allocates no device memory and keeps no state between calls, with
+ *    two exceptions: the text behind ck_last_error_detail() (one buffer per host
+ *    thread) and the built-in scratch buffer of ck_sparse_decode_attn_static.
  *  - A "head-problem" is one (sequence s, KV head h) pair, linear index
  *    hp = s * Hkv + h.  Query head hq belongs to KV head hq / (Hq / Hkv).
  *  - All tensors are row-major with the last dimension contiguous:
@@ -247,6 +249,29 @@ int ck_sparse_decode_attn(const ck_shape* sh, const void* q, const void* K, cons
                           int32_t max_tokens, int64_t n_sink, int64_t recent_begin,
                           int64_t recent_end, float softmax_scale, void* out, void* workspace,
                           size_t workspace_bytes, void* stream);
+
+/*
+ * ck_sparse_decode_attn for callers that cannot allocate device memory or hand
+ * over a workspace: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid allocation.  Same arguments, same kernels and the same result as
+ * ck_sparse_decode_attn; the split partials live in a buffer of
+ * CK_STATIC_SCRATCH_BYTES that is part of the library's code object (each GPU
+ * the library runs on holds its own copy until the process ends).  The call
+ * allocates and frees nothing.
+ *  - A shape whose partials exceed the buffer (ck_workspace_bytes(sh,
+ *    CK_WS_SPARSE_ATTN, ...) > CK_STATIC_SCRATCH_BYTES) is rejected with
+ *    CK_EWORKSPACE before anything is enqueued.
+ *  - All calls on one GPU share the buffer.  It keeps the last call's contents;
+ *    nothing in it has to start at zero (every partial is written before it is
+ *    read).  Calls of this entry point that overlap on one GPU (different
+ *    streams, no ordering between them) race on the buffer: order them.
+ */
+#define CK_STATIC_SCRATCH_BYTES (4u << 20)
+int ck_sparse_decode_attn_static(const ck_shape* sh, const void* q, const void* K, const void* V,
+                                 const int32_t* token_idx, const int32_t* n_tokens,
+                                 int32_t idx_stride, int32_t max_tokens, int64_t n_sink,
+                                 int64_t recent_begin, int64_t recent_end, float softmax_scale,
+                                 void* out, void* stream);
 
 /*
  * One whole decode step (Sections III-C, IV-C and II-B in one call): the same

@@ -357,6 +357,51 @@ int ck_sparse_decode_attn(const ck_shape* sh, const void* q, const void* K, cons
                     "attention launch");
 }
 
+int ck_sparse_decode_attn_static(const ck_shape* sh, const void* q, const void* K, const void* V,
+                                 const int32_t* token_idx, const int32_t* n_tokens,
+                                 int32_t idx_stride, int32_t max_tokens, int64_t n_sink,
+                                 int64_t recent_begin, int64_t recent_end, float softmax_scale,
+                                 void* out, void* stream) {
+  ck::Dims dm;
+  int rc = check_shape(sh, &dm, false);
+  if (rc) return rc;
+  if (n_sink < 0 || n_sink > sh->N_cap)
+    return fail(CK_EINVALID, "n_sink=%lld outside [0, N_cap]", (long long)n_sink);
+  if (recent_end < recent_begin) recent_end = recent_begin;
+  if (recent_begin < 0 || recent_end > sh->N_cap)
+    return fail(CK_EINVALID, "recent window [%lld, %lld) outside [0, N_cap]",
+                (long long)recent_begin, (long long)recent_end);
+  if (max_tokens < 0) return fail(CK_EINVALID, "max_tokens=%d is negative", max_tokens);
+  if (!n_tokens) max_tokens = 0;
+  if (n_tokens && max_tokens > 0) {
+    if (!token_idx) return fail(CK_EINVALID, "token_idx is NULL but n_tokens is given");
+    if (idx_stride < max_tokens)
+      return fail(CK_EINVALID, "idx_stride=%d smaller than max_tokens=%d", idx_stride, max_tokens);
+  }
+  if (!(softmax_scale > 0.f)) return fail(CK_EINVALID, "softmax_scale must be positive");
+  CK_REQUIRE_PTR(q);
+  CK_REQUIRE_PTR(K);
+  CK_REQUIRE_PTR(V);
+  CK_REQUIRE_PTR(out);
+  CK_OPTIONAL_PTR(token_idx);
+  CK_OPTIONAL_PTR(n_tokens);
+  const int64_t max_total = (int64_t)max_tokens + n_sink + (recent_end - recent_begin);
+  if (max_total > (int64_t)1 << 30) return fail(CK_EUNSUPPORTED, "attended set too large");
+  const size_t need = ck::attn_workspace_bytes(dm, max_total);
+  if (need > (size_t)CK_STATIC_SCRATCH_BYTES)
+    return fail(CK_EWORKSPACE,
+                "this shape needs %zu bytes of scratch, the built-in buffer holds %zu: use "
+                "ck_sparse_decode_attn with a workspace",
+                need, (size_t)CK_STATIC_SCRATCH_BYTES);
+  void* ws = nullptr;
+  const hipError_t e = ck::attn_static_scratch(&ws);
+  if (e != hipSuccess) return hip_result(e, "address of the built-in scratch buffer");
+  return hip_result(ck::launch_sparse_attn(dm, q, K, V, token_idx, n_tokens, idx_stride,
+                                           max_total, n_sink, recent_begin, recent_end,
+                                           softmax_scale, out, ws, (hipStream_t)stream),
+                    "attention launch");
+}
+
 int ck_decode_step(const ck_shape* sh, const void* q, const void* K, const void* V,
                    const void* centroids, const int32_t* sizes, const int32_t* offsets,
                    const int32_t* sorted_idx, int32_t n_clusters, int32_t budget, uint32_t flags,

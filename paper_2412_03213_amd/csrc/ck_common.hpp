@@ -235,6 +235,9 @@ hipError_t launch_expand_pages(int HP, const int32_t* page_idx, const int32_t* n
                                int32_t* n_tokens, hipStream_t st);
 int attn_num_splits(const Dims& dm, int64_t max_total);
 size_t attn_workspace_bytes(const Dims& dm, int64_t max_total);
+// address, on the current device, of the library-owned scratch array
+// (CK_STATIC_SCRATCH_BYTES bytes); looked up once per device
+hipError_t attn_static_scratch(void** ptr);
 hipError_t launch_sparse_attn(const Dims& dm, const void* q, const void* K, const void* V,
                               const int32_t* token_idx, const int32_t* n_tokens, int idx_stride,
                               int64_t max_total, int64_t n_sink, int64_t recent_begin,

@@ -19,6 +19,7 @@
 // selection of the recalled cluster prefix from the precomputed scores and maps
 // its own positions through the cluster-contiguous index directly; the index
 // list is still written out (each workgroup its own part) but never re-read.
+#include <mutex>
 #include <type_traits>
 
 #include "decode_common.hpp"
@@ -537,6 +538,35 @@ hipError_t launch_sparse_attn(const Dims& dm, const void* q, const void* K, cons
   a.n_tokens = n_tokens;
   if (dm.dtype == CK_BF16) return launch_attn_t<bf16, false>(dm, a, max_total, st);
   return launch_attn_t<float, false>(dm, a, max_total, st);
+}
+
+// ---- library-owned scratch for callers that cannot allocate ----
+// The split partials of one attention call, in device memory that exists from the
+// moment the code object is loaded: every GPU the library runs on holds its own
+// copy of the array until the process ends.  Host code never passes the array's
+// name anywhere; it asks the runtime once per device for the array's address on
+// that device and uses that pointer from then on.
+static __device__ __align__(256) unsigned char scratch[CK_STATIC_SCRATCH_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[MAX_DEVICES];                // address of `scratch` per device
+
+hipError_t attn_static_scratch(void** ptr) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return hipSuccess;
 }
 
 hipError_t launch_decode_fused(const Dims& dm, const void* q, const void* K, const void* V,

@@ -162,6 +162,29 @@ def test_argument_validation_without_a_device():
     expect(-3, attn, ws=None)
     expect(-4, attn, V=A + 2)
 
+    # the same call on the built-in scratch buffer: same validation, and shapes whose
+    # partials exceed the buffer are rejected before anything touches a device
+    def attn_static(**kw):
+        args = dict(sh=sh, q=A, K=A, V=A, idx=A, n=A, stride=1024, mx=1024, sink=0, rb=0, re=0,
+                    scale=0.088, out=A)
+        args.update(kw)
+        s = args["sh"].c()
+        rc = lib.ck_sparse_decode_attn_static(ctypes.byref(s), args["q"], args["K"], args["V"],
+                                              args["idx"], args["n"], args["stride"], args["mx"],
+                                              args["sink"], args["rb"], args["re"],
+                                              args["scale"], args["out"], None)
+        if rc:
+            raise ck.ClusterKVError(rc, lib.ck_strerror(rc).decode(),
+                                    lib.ck_last_error_detail().decode())
+
+    expect(-1, attn_static, out=None)
+    expect(-1, attn_static, sink=1001)
+    expect(-1, attn_static, stride=512)
+    expect(-4, attn_static, V=A + 2)
+    big = ck.Shape(512, 32, 8, 4096, 40)                            # 4096 head-problems x 4 heads
+    assert ck.ck_workspace_bytes(big, binding.CK_WS_SPARSE_ATTN, 1024) > (4 << 20)
+    expect(-3, attn_static, sh=big)
+
     # evaluation entry points
     expect(-1, ck.ck_full_decode_attn, sh, A, A, A, 0, A, workspace=A)
     expect(-1, ck.ck_full_decode_attn, sh, A, A, A, 1001, A, workspace=A)
