@@ -242,7 +242,11 @@ int ck_gather_indices(const ck_shape* sh, const int32_t* sel_clusters,
  * n_tokens  [dev] int32 [S, Hkv], nullable = no recalled tokens;
  * max_tokens  host upper bound of every n_tokens entry (e.g. the budget);
  * workspace [dev] ck_workspace_bytes(sh, CK_WS_SPARSE_ATTN,
- *           max_tokens + n_sink + recent_end - recent_begin, 0).
+ *           max_tokens + n_sink + recent_end - recent_begin, 0); its contents on
+ *           entry do not matter (nothing has to be zero).
+ * One launch: the attended positions of a head-problem are split over several
+ * workgroups, and the workgroup that finishes last merges the partial results
+ * (in split order, so the output does not depend on which one it is).
  */
 int ck_sparse_decode_attn(const ck_shape* sh, const void* q, const void* K, const void* V,
                           const int32_t* token_idx, const int32_t* n_tokens, int32_t idx_stride,
@@ -251,10 +255,22 @@ int ck_sparse_decode_attn(const ck_shape* sh, const void* q, const void* K, cons
                           size_t workspace_bytes, void* stream);
 
 /*
+ * The same attention with the partial results merged by a second kernel launch
+ * instead of by the last workgroup: the reference form of the merge (bit-identical
+ * output), kept for checking the single-launch form and for timing comparisons.
+ */
+int ck_sparse_decode_attn_two_pass(const ck_shape* sh, const void* q, const void* K,
+                                   const void* V, const int32_t* token_idx,
+                                   const int32_t* n_tokens, int32_t idx_stride,
+                                   int32_t max_tokens, int64_t n_sink, int64_t recent_begin,
+                                   int64_t recent_end, float softmax_scale, void* out,
+                                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * ck_sparse_decode_attn for callers that cannot allocate device memory or hand
  * over a workspace: code under HIP graph capture, tight serving loops, harnesses
  * that forbid allocation.  Same arguments, same kernels and the same result as
- * ck_sparse_decode_attn; the split partials live in a buffer of
+ * ck_sparse_decode_attn; the split partials and tickets live in a buffer of
  * CK_STATIC_SCRATCH_BYTES that is part of the library's code object (each GPU
  * the library runs on holds its own copy until the process ends).  The call
  * allocates and frees nothing.
@@ -277,10 +293,12 @@ int ck_sparse_decode_attn_static(const ck_shape* sh, const void* q, const void* 
  * One whole decode step (Sections III-C, IV-C and II-B in one call): the same
  * results as ck_select_clusters, ck_gather_indices and ck_sparse_decode_attn in
  * sequence (scores, sel_clusters, n_sel_clusters, n_sel_tokens, token_idx,
- * n_tokens, out; integer outputs identical, `out` identical up to the order of
- * fp32 additions), with fewer launches: the cluster scores are computed by one
- * kernel, and every attention workgroup then derives the recalled prefix and its
- * own slice of the index list itself instead of re-reading them from memory.
+ * n_tokens, out; all outputs bit-identical to the three calls), in ONE launch when
+ * the table is bf16 with at most 512 clusters: every attention workgroup scores
+ * the centroids of its head-problem, derives the recalled prefix and its own slice
+ * of the index list itself instead of re-reading them from memory, and the last
+ * workgroup of a head-problem merges.  Larger or fp32 tables are scored by a
+ * launch of their own first.
  * Arguments as in the three calls; idx_stride >= budget and a multiple of 4;
  * workspace: ck_workspace_bytes(sh, CK_WS_SPARSE_ATTN, budget + n_sink + recent
  * window, 0).

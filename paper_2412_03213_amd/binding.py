@@ -23,7 +23,7 @@ LIB_PATH = os.path.join(_PKG, "libclusterkv.so")
 
 EXPORTS = ("ck_version", "ck_strerror", "ck_last_error_detail", "ck_workspace_bytes",
            "ck_cluster_keys", "ck_cluster_keys_opt", "ck_kmeans_assign", "ck_build_metadata", "ck_kmeans_update",
-           "ck_select_clusters", "ck_gather_indices", "ck_sparse_decode_attn", "ck_sparse_decode_attn_static", "ck_decode_step",
+           "ck_select_clusters", "ck_gather_indices", "ck_sparse_decode_attn", "ck_sparse_decode_attn_static", "ck_sparse_decode_attn_two_pass", "ck_decode_step",
            "ck_full_decode_attn", "ck_token_scores", "ck_topk_select", "ck_recall_hits",
            "ck_page_keys", "ck_expand_pages", "ck_host_device_ptr", "ck_cache_reset",
            "ck_cached_decode_step", "ck_probe_mfma_bf16")
@@ -109,6 +109,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.ck_sparse_decode_attn.restype = ctypes.c_int
     lib.ck_sparse_decode_attn.argtypes = [SH, P, P, P, P, P, I32, I32, I64, I64, I64, F, P, P,
                                           SZ, P]
+    lib.ck_sparse_decode_attn_two_pass.restype = ctypes.c_int
+    lib.ck_sparse_decode_attn_two_pass.argtypes = lib.ck_sparse_decode_attn.argtypes
     lib.ck_sparse_decode_attn_static.restype = ctypes.c_int
     lib.ck_sparse_decode_attn_static.argtypes = [SH, P, P, P, P, P, I32, I32, I64, I64, I64, F, P, P]
     lib.ck_decode_step.restype = ctypes.c_int
@@ -260,7 +262,9 @@ def ck_gather_indices(sh: Shape, sel_clusters, n_sel_clusters, offsets, sorted_i
 
 
 def ck_sparse_decode_attn(sh: Shape, q, K, V, token_idx, n_tokens, max_tokens, out, n_sink=0,
-                          recent_begin=0, recent_end=0, softmax_scale=None, workspace=None):
+                          recent_begin=0, recent_end=0, softmax_scale=None, workspace=None,
+                          two_pass=False):
+    """two_pass=True calls ck_sparse_decode_attn_two_pass (merge by a second launch)."""
     lib = load_library()
     if softmax_scale is None:
         softmax_scale = sh.d ** -0.5
@@ -270,11 +274,11 @@ def ck_sparse_decode_attn(sh: Shape, q, K, V, token_idx, n_tokens, max_tokens, o
             ck_workspace_bytes(sh, CK_WS_SPARSE_ATTN, max_tokens + n_sink + n_recent), q)
     stride = token_idx.shape[-1] if isinstance(token_idx, torch.Tensor) else 0
     s = sh.c()
-    _check(lib.ck_sparse_decode_attn(ctypes.byref(s), _ptr(q), _ptr(K), _ptr(V), _ptr(token_idx),
-                                     _ptr(n_tokens), stride, max_tokens, n_sink, recent_begin,
-                                     recent_end, softmax_scale, _ptr(out), _ptr(workspace),
-                                     workspace.numel() if isinstance(workspace, torch.Tensor)
-                                     else 0, _stream(q)))
+    fn = lib.ck_sparse_decode_attn_two_pass if two_pass else lib.ck_sparse_decode_attn
+    _check(fn(ctypes.byref(s), _ptr(q), _ptr(K), _ptr(V), _ptr(token_idx), _ptr(n_tokens), stride,
+              max_tokens, n_sink, recent_begin, recent_end, softmax_scale, _ptr(out),
+              _ptr(workspace), workspace.numel() if isinstance(workspace, torch.Tensor) else 0,
+              _stream(q)))
     return workspace
 
 

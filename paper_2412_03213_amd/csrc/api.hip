@@ -316,7 +316,7 @@ int ck_gather_indices(const ck_shape* sh, const int32_t* sel_clusters,
                     "gather launch");
 }
 
-int ck_sparse_decode_attn(const ck_shape* sh, const void* q, const void* K, const void* V,
+static int sparse_decode_attn(bool two_pass, const ck_shape* sh, const void* q, const void* K, const void* V,
                           const int32_t* token_idx, const int32_t* n_tokens, int32_t idx_stride,
                           int32_t max_tokens, int64_t n_sink, int64_t recent_begin,
                           int64_t recent_end, float softmax_scale, void* out, void* workspace,
@@ -353,8 +353,30 @@ int ck_sparse_decode_attn(const ck_shape* sh, const void* q, const void* K, cons
     return fail(CK_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
   return hip_result(ck::launch_sparse_attn(dm, q, K, V, token_idx, n_tokens, idx_stride,
                                            max_total, n_sink, recent_begin, recent_end,
-                                           softmax_scale, out, workspace, (hipStream_t)stream),
+                                           softmax_scale, out, workspace, two_pass,
+                                           (hipStream_t)stream),
                     "attention launch");
+}
+
+int ck_sparse_decode_attn(const ck_shape* sh, const void* q, const void* K, const void* V,
+                          const int32_t* token_idx, const int32_t* n_tokens, int32_t idx_stride,
+                          int32_t max_tokens, int64_t n_sink, int64_t recent_begin,
+                          int64_t recent_end, float softmax_scale, void* out, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+  return sparse_decode_attn(false, sh, q, K, V, token_idx, n_tokens, idx_stride, max_tokens,
+                            n_sink, recent_begin, recent_end, softmax_scale, out, workspace,
+                            workspace_bytes, stream);
+}
+
+int ck_sparse_decode_attn_two_pass(const ck_shape* sh, const void* q, const void* K,
+                                   const void* V, const int32_t* token_idx,
+                                   const int32_t* n_tokens, int32_t idx_stride,
+                                   int32_t max_tokens, int64_t n_sink, int64_t recent_begin,
+                                   int64_t recent_end, float softmax_scale, void* out,
+                                   void* workspace, size_t workspace_bytes, void* stream) {
+  return sparse_decode_attn(true, sh, q, K, V, token_idx, n_tokens, idx_stride, max_tokens,
+                            n_sink, recent_begin, recent_end, softmax_scale, out, workspace,
+                            workspace_bytes, stream);
 }
 
 int ck_sparse_decode_attn_static(const ck_shape* sh, const void* q, const void* K, const void* V,
@@ -398,7 +420,7 @@ int ck_sparse_decode_attn_static(const ck_shape* sh, const void* q, const void* 
   if (e != hipSuccess) return hip_result(e, "address of the built-in scratch buffer");
   return hip_result(ck::launch_sparse_attn(dm, q, K, V, token_idx, n_tokens, idx_stride,
                                            max_total, n_sink, recent_begin, recent_end,
-                                           softmax_scale, out, ws, (hipStream_t)stream),
+                                           softmax_scale, out, ws, false, (hipStream_t)stream),
                     "attention launch");
 }
 
@@ -480,7 +502,8 @@ int ck_full_decode_attn(const ck_shape* sh, const void* q, const void* K, const 
     return fail(CK_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
   // the leading "sink" range of the attended set, stretched over the whole context
   return hip_result(ck::launch_sparse_attn(dm, q, K, V, nullptr, nullptr, 0, n_ctx, n_ctx, 0, 0,
-                                           softmax_scale, out, workspace, (hipStream_t)stream),
+                                           softmax_scale, out, workspace, false,
+                                           (hipStream_t)stream),
                     "full attention launch");
 }
 
@@ -692,7 +715,8 @@ int ck_cached_decode_step(const ck_shape* sh, const void* q, const void* K_home,
   if (e != hipSuccess) return hip_result(e, "cache fill launch");
   // attention over the first n_sel_tokens rows of the new generation
   return hip_result(ck::launch_sparse_attn(dc, q, cache->K[g], cache->V[g], nullptr, n_sel_tokens,
-                                           0, budget, 0, 0, 0, softmax_scale, out, workspace, st),
+                                           0, budget, 0, 0, 0, softmax_scale, out, workspace, false,
+                                           st),
                     "attention launch");
 }
 

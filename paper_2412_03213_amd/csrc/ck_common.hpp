@@ -242,6 +242,6 @@ hipError_t launch_sparse_attn(const Dims& dm, const void* q, const void* K, cons
                               const int32_t* token_idx, const int32_t* n_tokens, int idx_stride,
                               int64_t max_total, int64_t n_sink, int64_t recent_begin,
                               int64_t recent_end, float softmax_scale, void* out, void* workspace,
-                              hipStream_t st);
+                              bool two_pass, hipStream_t st);
 
 }  // namespace ck

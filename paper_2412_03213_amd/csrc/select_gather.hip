@@ -1,17 +1,20 @@
 // Cluster selection (paper Section III-C) and index generation (Section IV-C, Fig. 8).
+#include <type_traits>
+
 #include "decode_common.hpp"
 
 namespace ck {
 
 // ------------------------------------------------------------------ scoring
-// s_c = sum_g <q_g, mu_c> = <sum_g q_g, mu_c>.  The centroid table is the second
-// largest byte stream of a decode step, so it is spread over many workgroups
-// (64 rows each) instead of one per head-problem; 16 lanes share a row.
+// s_c = sum_g <q_g, mu_c>.  The centroid table is the second largest byte stream of a
+// decode step, so it is spread over many workgroups (64 or 256 rows each) instead of
+// one per head-problem.  bf16 tables go through the matrix cores (score_rows16: 16 rows
+// per wavefront step, all loads of a wavefront issued before the first use); fp32
+// tables (check mode) keep dot products on the vector ALUs, 16 lanes per row.
 constexpr int SCORE_THREADS = 256;
 
-// SCORE_ROWS centroid rows per workgroup: 64 when there are few head-problems (more
-// workgroups, lower latency), 256 when there are many (more bytes in flight per
-// workgroup, fewer workgroups to dispatch).
+// SCORE_ROWS rows per workgroup: 64 when there are few head-problems (more workgroups,
+// lower latency), 256 when there are many (more bytes in flight per workgroup).
 template <typename T, int SCORE_ROWS>
 __global__ __launch_bounds__(SCORE_THREADS) void k_score(
     const T* __restrict__ q, const T* __restrict__ table, int Hq, int Hkv, int G,
@@ -19,33 +22,56 @@ __global__ __launch_bounds__(SCORE_THREADS) void k_score(
     int64_t score_stride) {
   const int hp = blockIdx.y, tid = threadIdx.x;
   const int s = hp / Hkv, h = hp % Hkv;
-  const int l16 = tid & 15, grp = tid >> 4;                 // 16 groups of 16 lanes
   const int c0 = blockIdx.x * SCORE_ROWS;
-  const T* Chp = table + ((int64_t)hp * table_stride + row_begin) * D + l16 * 8;
-  float mv[SCORE_ROWS / 16][8];
+  if constexpr (std::is_same<T, bf16>::value) {
+    constexpr int U = SCORE_ROWS / 64;                      // 16-row steps per wavefront
+    const int lane = tid & 63, wave = tid >> 6, col = lane & 15, kg = lane >> 4;
+    bf16x8 qb[4];
+    load_query_operand(q + ((int64_t)s * Hq + h * G) * D, G, lane, qb);
+    const bf16* Thp = table + ((int64_t)hp * table_stride + row_begin) * D + kg * 8;
+    uint4 a[U][4];
 #pragma unroll
-  for (int u = 0; u < SCORE_ROWS / 16; ++u) {
-    int c = c0 + u * 16 + grp;
-    if (c >= n_rows) c = n_rows - 1;                       // clamp: result is discarded
-    load_row8<T>(Chp + (int64_t)c * D, mv[u]);
-  }
-  float qv[8];
+    for (int u = 0; u < U; ++u) {
+      int r = c0 + (u * 4 + wave) * 16 + col;
+      if (r >= n_rows) r = n_rows - 1;                      // clamp: result is discarded
 #pragma unroll
-  for (int j = 0; j < 8; ++j) qv[j] = 0.f;
-  for (int g = 0; g < G; ++g) {
-    float t[8];
-    load_row8<T>(q + ((int64_t)s * Hq + h * G + g) * D + l16 * 8, t);
+      for (int sl = 0; sl < 4; ++sl)
+        a[u][sl] = *reinterpret_cast<const uint4*>(Thp + (int64_t)r * D + sl * 32);
+    }
 #pragma unroll
-    for (int j = 0; j < 8; ++j) qv[j] += t[j];
-  }
+    for (int u = 0; u < U; ++u) {
+      const float v = score_rows16(a[u], qb, G);
+      const int r = c0 + (u * 4 + wave) * 16 + lane;
+      if (lane < 16 && r < n_rows) scores[(int64_t)hp * score_stride + row_begin + r] = v;
+    }
+  } else {
+    const int l16 = tid & 15, grp = tid >> 4;               // 16 groups of 16 lanes
+    const T* Chp = table + ((int64_t)hp * table_stride + row_begin) * D + l16 * 8;
+    float mv[SCORE_ROWS / 16][8];
 #pragma unroll
-  for (int u = 0; u < SCORE_ROWS / 16; ++u) {
-    const int c = c0 + u * 16 + grp;
-    float dot = 0.f;
+    for (int u = 0; u < SCORE_ROWS / 16; ++u) {
+      int c = c0 + u * 16 + grp;
+      if (c >= n_rows) c = n_rows - 1;                      // clamp: result is discarded
+      load_row8<T>(Chp + (int64_t)c * D, mv[u]);
+    }
+    float qv[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) dot = fmaf(qv[j], mv[u][j], dot);
-    dot = row16_sum(dot);
-    if (c < n_rows && l16 == 0) scores[(int64_t)hp * score_stride + row_begin + c] = dot;
+    for (int j = 0; j < 8; ++j) qv[j] = 0.f;
+    for (int g = 0; g < G; ++g) {
+      float t[8];
+      load_row8<T>(q + ((int64_t)s * Hq + h * G + g) * D + l16 * 8, t);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) qv[j] += t[j];
+    }
+#pragma unroll
+    for (int u = 0; u < SCORE_ROWS / 16; ++u) {
+      const int c = c0 + u * 16 + grp;
+      float dot = 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) dot = fmaf(qv[j], mv[u][j], dot);
+      dot = row16_sum(dot);
+      if (c < n_rows && l16 == 0) scores[(int64_t)hp * score_stride + row_begin + c] = dot;
+    }
   }
 }
 
@@ -79,13 +105,14 @@ hipError_t launch_score(const Dims& dm, const void* q, const void* centroids, in
 // ------------------------------------------------------------------ order + budget
 // One workgroup per head-problem, as in the paper (its kernels use one thread block
 // per KV head with the size metadata in shared memory).
+template <int CMAX>
 __global__ __launch_bounds__(SELP_THREADS) void k_rank(
     const float* __restrict__ scores, const int32_t* __restrict__ sizes, int C_cap,
     int n_clusters, int budget, int trim, int32_t* __restrict__ sel_clusters,
     int32_t* __restrict__ n_sel_clusters, int32_t* __restrict__ n_sel_tokens) {
-  __shared__ SelectLds L;
+  __shared__ SelectLds<CMAX> L;
   const int hp = blockIdx.x, tid = threadIdx.x;
-  select_prefix(L, scores + (int64_t)hp * C_cap, sizes + (int64_t)hp * C_cap, nullptr,
+  select_prefix<CMAX>(L, scores + (int64_t)hp * C_cap, sizes + (int64_t)hp * C_cap, nullptr,
                 n_clusters, budget, trim);
   const int n_sel = L.n_sel;
   for (int j = tid; j < n_sel; j += SELP_THREADS) sel_clusters[(int64_t)hp * C_cap + j] = L.ord[j];
@@ -101,9 +128,14 @@ hipError_t launch_select(const Dims& dm, const void* q, const void* centroids,
                          float* scores, hipStream_t st) {
   hipError_t e = launch_score(dm, q, centroids, n_clusters, scores, st);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(k_rank, dim3(dm.HP), dim3(SELP_THREADS), 0, st, scores, sizes, dm.C_cap,
-                     n_clusters, budget, (int)(flags & CK_SEL_TRIM_LAST), sel_clusters,
-                     n_sel_clusters, n_sel_tokens);
+  if (n_clusters <= SELP_SMALL)
+    hipLaunchKernelGGL(k_rank<SELP_SMALL>, dim3(dm.HP), dim3(SELP_THREADS), 0, st, scores, sizes,
+                       dm.C_cap, n_clusters, budget, (int)(flags & CK_SEL_TRIM_LAST),
+                       sel_clusters, n_sel_clusters, n_sel_tokens);
+  else
+    hipLaunchKernelGGL(k_rank<CK_MAX_CLUSTERS>, dim3(dm.HP), dim3(SELP_THREADS), 0, st, scores,
+                       sizes, dm.C_cap, n_clusters, budget, (int)(flags & CK_SEL_TRIM_LAST),
+                       sel_clusters, n_sel_clusters, n_sel_tokens);
   return hipGetLastError();
 }
 

@@ -1,6 +1,7 @@
 // Sparse GQA decode attention over the recalled tokens (paper Section II-B:
 // softmax(q K_S^T / sqrt(d)) V_S with K_S, V_S the selected rows), alone or fused
-// with the cluster selection and index generation of Sections III-C / IV-C.
+// with the centroid scoring and cluster selection of Section III-C and the index
+// generation of Section IV-C: a whole decode step is then ONE kernel launch.
 //
 // HBM-bound: every recalled K and V row (256 B in bf16) is read exactly once per
 // KV head and shared by the G query heads of the group.  A wavefront takes 16
@@ -10,15 +11,25 @@
 // which removes the unpacking, the dot products and their cross-lane reductions
 // from the vector ALUs (fp32 check mode keeps the all-VALU form).  The attended
 // positions of a head-problem are split over several workgroups (split-KV) so that
-// a batch of a few sequences still fills 256 CUs, and a small second kernel merges
-// the partial (max, sum, accumulator) triples.  Inside a workgroup the token rows
-// of its positions are resolved into LDS first, so the K/V loads of the next step
-// are always in flight while the current one is reduced.
+// a batch of a few sequences still fills 256 CUs.  Inside a workgroup the token rows
+// of its positions are resolved into LDS first, and the K/V loads of the next TWO
+// steps are in flight while the current one is reduced.
 //
-// Fused mode: every workgroup of a head-problem repeats the (cheap, LDS-only)
-// selection of the recalled cluster prefix from the precomputed scores and maps
-// its own positions through the cluster-contiguous index directly; the index
-// list is still written out (each workgroup its own part) but never re-read.
+// Merging the splits without a second launch: every workgroup publishes its partial
+// (max, sum, accumulator) with agent-scope stores, takes a ticket from a counter of
+// its head-problem, and the workgroup that draws the last ticket reads all partials
+// back with agent-scope loads and writes the output.  Nobody waits for anybody, so
+// nothing can hang; agent-scope accesses are performed past the XCD-private L2
+// caches, so no cache write-back or invalidate is needed.  The merge adds the
+// partials in split order, whoever runs it: results are bit-reproducible.
+//
+// Fused modes: every workgroup of a head-problem repeats the (cheap, LDS-only)
+// selection of the recalled cluster prefix and maps its own positions through the
+// cluster-contiguous index directly; the index list is still written out (each
+// workgroup its own part) but never re-read.  With at most 512 clusters in bf16 the
+// centroid scores are computed by every workgroup as well (the workgroups of one
+// head-problem are placed on one XCD, so the table comes from HBM once and out of
+// that XCD's L2 otherwise); larger or fp32 tables are scored by a launch of their own.
 #include <mutex>
 #include <type_traits>
 
@@ -29,11 +40,16 @@ namespace ck {
 constexpr int ATT_THREADS = SELP_THREADS;  // 4 wavefronts = 16 token slots per workgroup step
 constexpr int ATT_UNROLL = 4;              // token slots in flight per 16-lane group
 constexpr int ATT_STEP_TOKENS = 16 * ATT_UNROLL;   // 64 tokens per workgroup iteration
-constexpr int ATT_MAX_CHUNK = 4096;        // positions one workgroup may own (rows held in LDS)
+constexpr int ATT_MAX_CHUNK = 2048;        // positions one workgroup may own (rows held in LDS)
+constexpr int ATT_MAX_SPLITS = 1024;       // workgroups per head-problem
 constexpr float NEG_BIG = -1.0e30f;        // "no token yet": finite so that differences stay finite
 constexpr int ATT_TARGET_WGS = 512;        // 2 per CU on 256 CUs
-constexpr int PEX_WAVE = 16 * 8 + 8;             // floats of probability exchange per wavefront (G <= 8)
+constexpr int PEX_WAVE = 16 * 8 + 8;       // floats of probability exchange per wavefront (G <= 8)
 constexpr int PART_STRIDE = D + 2;         // floats per (split, query head): max, sum, acc[128]
+constexpr int N_XCD = 8;                   // workgroup i of a launch runs on XCD i % 8
+constexpr unsigned long long TICKET_MAGIC = 0x434B7469636Bull;   // marks a ticket word as ours
+
+enum { ATT_PLAIN = 0, ATT_FUSED = 1, ATT_FUSED_SCORE = 2 };
 
 template <typename T> struct RawRow;
 template <> struct RawRow<bf16> {
@@ -60,49 +76,199 @@ __device__ __forceinline__ void store_out(bf16* p, float v) {
 }
 __device__ __forceinline__ void store_out(float* p, float v) { *p = v; }
 
+// ---- partials in memory: pairs of floats, moved as one 64-bit word ----
+// Agent scope: the access is performed past the XCD-private L2, so a workgroup on
+// another XCD sees the value without any cache maintenance.
+__device__ __forceinline__ void put_pair_agent(float* p, float x, float y) {
+  const unsigned long long w =
+      (unsigned long long)__float_as_uint(x) | ((unsigned long long)__float_as_uint(y) << 32);
+  __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), w, __ATOMIC_RELAXED,
+                     __HIP_MEMORY_SCOPE_AGENT);
+}
+struct PairAgent {
+  __device__ __forceinline__ float2 operator()(const float* p) const {
+    const unsigned long long w =
+        __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED,
+                          __HIP_MEMORY_SCOPE_AGENT);
+    return make_float2(__uint_as_float((uint32_t)w), __uint_as_float((uint32_t)(w >> 32)));
+  }
+};
+struct PairPlain {
+  __device__ __forceinline__ float2 operator()(const float* p) const {
+    return *reinterpret_cast<const float2*>(p);
+  }
+};
+
+// out channels (c2, c2 + 1) of one query head from its n_split partials:
+//   sum_i acc_i 2^(m_i - M) / sum_i l_i 2^(m_i - M), splits added in index order,
+// MERGE_BATCH partials loaded together so that their latencies overlap.
+// base = partial of split 0 for this head, stride = floats between splits.
+constexpr int MERGE_BATCH = 16;
+template <typename Load>
+__device__ __forceinline__ float2 merge_splits(const float* base, int64_t stride, int n_split,
+                                               int c2, Load load) {
+  float M = NEG_BIG, ls = 0.f, a0 = 0.f, a1 = 0.f;
+  for (int i0 = 0; i0 < n_split; i0 += MERGE_BATCH) {
+    float2 ml[MERGE_BATCH], av[MERGE_BATCH];
+#pragma unroll
+    for (int i = 0; i < MERGE_BATCH; ++i) {
+      const bool ok = i0 + i < n_split;
+      const float* p = base + (int64_t)(ok ? i0 + i : 0) * stride;
+      ml[i] = load(p);
+      av[i] = load(p + 2 + c2);
+      if (!ok) {
+        ml[i] = make_float2(NEG_BIG, 0.f);
+        av[i] = make_float2(0.f, 0.f);
+      }
+    }
+    float mx = M;
+#pragma unroll
+    for (int i = 0; i < MERGE_BATCH; ++i) mx = fmaxf(mx, ml[i].x);
+    const float corr = __builtin_amdgcn_exp2f(M - mx);
+    ls *= corr;
+    a0 *= corr;
+    a1 *= corr;
+    M = mx;
+#pragma unroll
+    for (int i = 0; i < MERGE_BATCH; ++i) {
+      const float f = __builtin_amdgcn_exp2f(ml[i].x - mx);
+      ls += ml[i].y * f;
+      a0 += av[i].x * f;
+      a1 += av[i].y * f;
+    }
+  }
+  const float inv = ls > 0.f ? 1.0f / ls : 0.f;
+  return make_float2(a0 * inv, a1 * inv);
+}
+
 struct AttnArgs {
   const void *q, *K, *V;
   void* out;
-  float* part;
+  float* part;                  // [HP, n_split, G, PART_STRIDE]
+  unsigned long long* tickets;  // [HP]: (TICKET_MAGIC << 16) | workgroups arrived so far
   // given index list
   const int32_t* token_idx;
   const int32_t* n_tokens;
   // fused selection
-  const float* scores;
+  const void* centroids;        // ATT_FUSED_SCORE: the table to score
+  float* scores;                // ATT_FUSED: read; ATT_FUSED_SCORE: written
   const int32_t *sizes, *offsets, *sorted_idx;
   int32_t *sel_clusters, *n_sel_clusters, *n_sel_tokens, *token_idx_out, *n_tokens_out;
   int n_clusters, budget, trim, C_cap;
   // common
-  int idx_stride, max_tokens, Hq, Hkv, n_sink, n_recent, chunk, n_split;
+  int HP, idx_stride, max_tokens, Hq, Hkv, n_sink, n_recent, chunk, n_split, two_pass;
   int64_t N_cap, recent_begin;
   float scale_log2e;
 };
 
-template <int G>
-struct AttnPlainLds {
-  int rows[ATT_MAX_CHUNK];
-  float red[4 * G * PART_STRIDE];
-};
+template <int G> struct PlainLds { float red[4 * G * PART_STRIDE]; };
 
 // Attended position p of a head-problem -> token row:
 //   [0, n_sink) sinks, then the recalled list, then [recent_begin, recent_end).
-template <typename T, int G, bool FUSED>
-__global__ __launch_bounds__(ATT_THREADS) void k_attn_partial(const AttnArgs a) {
-  using Lds = typename std::conditional<FUSED, SelectLds, AttnPlainLds<G>>::type;
-  __shared__ Lds lds;
+// One-dimensional grid: workgroup i runs on XCD i % 8 (round-robin dispatch), so the
+// n_split workgroups of a head-problem are given ids of one residue class and share
+// that XCD's L2 (sizes, offsets, scores or the centroid table).  Placement only affects
+// speed, never results.
+template <typename T, int G, int MODE, int CMAX>
+__global__ __launch_bounds__(ATT_THREADS) void k_attn(const AttnArgs a) {
+  constexpr bool FUSED = MODE != ATT_PLAIN;
+  using Big = typename std::conditional<FUSED, SelectLds<CMAX>, PlainLds<G>>::type;
+  static_assert(sizeof(Big) >= sizeof(PlainLds<G>), "the wavefront partials reuse the selection's LDS");
+  __shared__ Big big;                                   // selection, later the wavefront partials
+  __shared__ int rows[ATT_MAX_CHUNK];
   __shared__ __attribute__((aligned(16))) float pex[4 * PEX_WAVE];
-  int* rows;
-  float* red;
-  const int split = blockIdx.x, hp = blockIdx.y, tid = threadIdx.x;
+  __shared__ __attribute__((aligned(16))) float sc_lds[MODE == ATT_FUSED_SCORE ? CMAX : 4];
+  __shared__ int s_last;
+  float* red = reinterpret_cast<float*>(&big);
+
+  // one argument per 64-byte line of the argument block: all lines are requested now
+  CK_FETCH_ARG(a.q);
+  CK_FETCH_ARG(a.n_tokens);
+  CK_FETCH_ARG(a.sorted_idx);
+  CK_FETCH_ARG(a.n_tokens_out);
+  CK_FETCH_ARG(a.n_clusters);
+  CK_FETCH_ARG(a.C_cap);
+  CK_FETCH_ARG(a.n_sink);
+  CK_FETCH_ARG(a.scale_log2e);
+  const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6, l16 = tid & 15, slot = tid >> 4;  // 16 slots
+  const int wg = blockIdx.x, xcd = wg % N_XCD, seq = wg / N_XCD;
+  const int hp = (seq / a.n_split) * N_XCD + xcd, split = seq % a.n_split;
+  if (hp >= a.HP) return;                               // the grid is padded to whole groups of 8
   const int s = hp / a.Hkv, h = hp % a.Hkv;
   const T* q = static_cast<const T*>(a.q);
 
+  // the query heads of the group as an MFMA operand (bf16): for the scores and for q K^T
+  bf16x8 qb[4];
+  if constexpr (std::is_same<T, bf16>::value)
+    load_query_operand(reinterpret_cast<const bf16*>(q) + ((int64_t)s * a.Hq + h * G) * D, G, lane, qb);
+
   int n_idx;
   if constexpr (FUSED) {
-    SelectLds& L = lds;
-    select_prefix(L, a.scores + (int64_t)hp * a.C_cap, a.sizes + (int64_t)hp * a.C_cap,
-                  a.offsets + (int64_t)hp * (a.C_cap + 1), a.n_clusters, a.budget, a.trim);
+    SelectLds<CMAX>& L = big;
+    if constexpr (MODE == ATT_FUSED_SCORE) {
+      // ---- scores of all clusters of this head-problem (bf16 table, matrix cores) ----
+      // Every load of the prologue is issued before the first use: the table rows of
+      // this wavefront (16 rows per step, steps wave, wave + 4, ...), the query heads,
+      // the sizes and offsets this thread will bring to the selection: one round trip.
+      constexpr int ITEMS = CMAX / SELP_THREADS;
+      constexpr int SB = CMAX / 64;                     // 16-row steps per wavefront
+      const int col = lane & 15, kg = lane >> 4;
+      int sz[ITEMS], of[ITEMS];
+#pragma unroll
+      for (int i = 0; i < ITEMS; ++i) {
+        const int c = tid + i * SELP_THREADS;
+        sz[i] = c < a.n_clusters ? a.sizes[(int64_t)hp * a.C_cap + c] : 0;
+        of[i] = c < a.n_clusters ? a.offsets[(int64_t)hp * (a.C_cap + 1) + c] : 0;
+      }
+      const bf16* Thp = static_cast<const bf16*>(a.centroids) + (int64_t)hp * a.C_cap * D + kg * 8;
+      const int n_steps = (a.n_clusters + 15) >> 4;
+      uint4 ar[SB][4];
+#pragma unroll
+      for (int u = 0; u < SB; ++u) {
+        if (wave + 4 * u < n_steps) {                   // wave-uniform
+          int r = (wave + 4 * u) * 16 + col;
+          if (r >= a.n_clusters) r = a.n_clusters - 1;  // clamp: result is discarded
+#pragma unroll
+          for (int sl = 0; sl < 4; ++sl)
+            ar[u][sl] = *reinterpret_cast<const uint4*>(Thp + (int64_t)r * D + sl * 32);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < SB; ++u) {
+        if (wave + 4 * u < n_steps) {
+          const float v = score_rows16(ar[u], qb, G);
+          const int r = (wave + 4 * u) * 16 + lane;
+          if (lane < 16 && r < a.n_clusters) {
+            sc_lds[r] = v;
+            if (split == 0) a.scores[(int64_t)hp * a.C_cap + r] = v;
+          }
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < ITEMS; ++i) {
+        const int c = tid + i * SELP_THREADS;
+        if (c < a.n_clusters) {
+          L.ssz[c] = sz[i];
+          L.soff[c] = of[i];
+        }
+      }
+      __syncthreads();
+      // one wavefront selects when a few dozen candidates bound the prefix (the usual
+      // case); otherwise all four do, the general way
+      if (!select_prefix_wave(L, sc_lds, a.n_clusters, a.budget, a.trim)) {
+        float sc[ITEMS];
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+          const int c = tid + i * SELP_THREADS;
+          sc[i] = c < a.n_clusters ? sc_lds[c] : 0.f;
+        }
+        select_prefix_regs<CMAX>(L, sc, sz, of, true, a.n_clusters, a.budget, a.trim);
+      }
+    } else {
+      select_prefix<CMAX>(L, a.scores + (int64_t)hp * a.C_cap, a.sizes + (int64_t)hp * a.C_cap,
+                          a.offsets + (int64_t)hp * (a.C_cap + 1), a.n_clusters, a.budget, a.trim);
+    }
     n_idx = L.n_tok;
     if (split == 0) {
       for (int j = tid; j < L.n_sel; j += ATT_THREADS)
@@ -113,11 +279,7 @@ __global__ __launch_bounds__(ATT_THREADS) void k_attn_partial(const AttnArgs a) 
         a.n_tokens_out[hp] = n_idx;
       }
     }
-    rows = reinterpret_cast<int*>(L.key);               // key + ssz: free after the ranking
-    red = reinterpret_cast<float*>(L.ord);              // ord, cum, cbeg, cand: free once the rows are known
   } else {
-    rows = lds.rows;
-    red = lds.red;
     n_idx = a.n_tokens ? a.n_tokens[hp] : 0;
     n_idx = n_idx < 0 ? 0 : (n_idx > a.max_tokens ? a.max_tokens : n_idx);
   }
@@ -136,7 +298,7 @@ __global__ __launch_bounds__(ATT_THREADS) void k_attn_partial(const AttnArgs a) 
     } else if (p < a.n_sink + n_idx) {
       const int qpos = p - a.n_sink;
       if constexpr (FUSED) {
-        SelectLds& L = lds;
+        SelectLds<CMAX>& L = big;
         // smallest j with cum[j] > qpos (empty clusters in the prefix are skipped)
         int lo = 0, hi = L.n_sel - 1;
         while (lo < hi) {
@@ -163,7 +325,7 @@ __global__ __launch_bounds__(ATT_THREADS) void k_attn_partial(const AttnArgs a) 
     row = row < 0 ? 0 : (row >= a.N_cap ? a.N_cap - 1 : row);
     rows[i] = (int)row;
   }
-  __syncthreads();
+  __syncthreads();                                      // rows complete; the selection's LDS is free
 
   float acc[G][8];
 #pragma unroll
@@ -183,37 +345,27 @@ __global__ __launch_bounds__(ATT_THREADS) void k_attn_partial(const AttnArgs a) 
     // bytes of wavefront-private LDS.  All four token slots of a wavefront share
     // one running max per head.
     const int col = lane & 15, kg = lane >> 4;          // kg is also this lane's slot in the wavefront
-    bf16x8 qb[4];
-#pragma unroll
-    for (int sl = 0; sl < 4; ++sl) {
-      uint4 w = make_uint4(0, 0, 0, 0);
-      if (col < G)
-        w = *reinterpret_cast<const uint4*>(q + ((int64_t)s * a.Hq + h * G + col) * D + sl * 32 + kg * 8);
-      qb[sl] = __builtin_bit_cast(bf16x8, w);
-    }
     float m_run = NEG_BIG, l_run = 0.f;                 // of head `col`, identical in its four lanes
     float* px = pex + wave * PEX_WAVE;                  // [slot][u][g] probabilities, then [g] rescale factors
     const bf16* Khp = static_cast<const bf16*>(a.K) + (int64_t)hp * a.N_cap * D + kg * 8;
     const int tpos = (col >> 2) * 16 + wave * 4 + (col & 3);   // A row `col` = token (u = col/4, slot = col%4)
-    uint4 kc[4], kn[4], vc[ATT_UNROLL], vn[ATT_UNROLL];
-    auto fetch = [&](int i0, uint4(&kr)[4], uint4(&vr)[ATT_UNROLL]) {
+    struct Regs { uint4 k[4], v[ATT_UNROLL]; };
+    auto fetch = [&](int i0, Regs& r) {
       const int ik = i0 + tpos;
       const bf16* kp = Khp + (int64_t)(ik < n_pos ? rows[ik] : 0) * D;
 #pragma unroll
-      for (int sl = 0; sl < 4; ++sl) kr[sl] = *reinterpret_cast<const uint4*>(kp + sl * 32);
+      for (int sl = 0; sl < 4; ++sl) r.k[sl] = *reinterpret_cast<const uint4*>(kp + sl * 32);
 #pragma unroll
       for (int u = 0; u < ATT_UNROLL; ++u) {
         const int i = i0 + u * 16 + slot;
-        vr[u] = *reinterpret_cast<const uint4*>(Vhp + (int64_t)(i < n_pos ? rows[i] : 0) * D);
+        r.v[u] = *reinterpret_cast<const uint4*>(Vhp + (int64_t)(i < n_pos ? rows[i] : 0) * D);
       }
     };
-    if (n_pos > 0) fetch(0, kc, vc);
-    for (int i0 = 0; i0 < n_pos; i0 += ATT_STEP_TOKENS) {
-      if (i0 + ATT_STEP_TOKENS < n_pos) fetch(i0 + ATT_STEP_TOKENS, kn, vn);
+    auto reduce = [&](int i0, const Regs& r) {
       floatx4 d = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int sl = 0; sl < 4; ++sl)
-        d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kc[sl]), qb[sl], d, 0, 0, 0);
+        d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, r.k[sl]), qb[sl], d, 0, 0, 0);
       // d[i]: token (u = kg, slot i) against head `col`
       float sc[4];
       const int ibase = i0 + kg * 16 + wave * 4;
@@ -260,21 +412,33 @@ __global__ __launch_bounds__(ATT_THREADS) void k_attn_partial(const AttnArgs a) 
 #pragma unroll
       for (int u = 0; u < ATT_UNROLL; ++u) {
         float vv[8];
-        vv[0] = lo_bf16(vc[u].x); vv[1] = hi_bf16(vc[u].x); vv[2] = lo_bf16(vc[u].y); vv[3] = hi_bf16(vc[u].y);
-        vv[4] = lo_bf16(vc[u].z); vv[5] = hi_bf16(vc[u].z); vv[6] = lo_bf16(vc[u].w); vv[7] = hi_bf16(vc[u].w);
+        vv[0] = lo_bf16(r.v[u].x); vv[1] = hi_bf16(r.v[u].x); vv[2] = lo_bf16(r.v[u].y); vv[3] = hi_bf16(r.v[u].y);
+        vv[4] = lo_bf16(r.v[u].z); vv[5] = hi_bf16(r.v[u].z); vv[6] = lo_bf16(r.v[u].w); vv[7] = hi_bf16(r.v[u].w);
 #pragma unroll
         for (int g = 0; g < G; ++g)
 #pragma unroll
           for (int j = 0; j < 8; ++j) acc[g][j] = fmaf(pr[u][g], vv[j], acc[g][j]);
       }
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        kc[u] = kn[u];
-        vc[u] = vn[u];
+    };
+    // three register sets in rotation: the loads of steps t + 1 and t + 2 are in flight
+    // while step t is reduced
+    Regs ra, rb, rc;
+    constexpr int ST = ATT_STEP_TOKENS;
+    if (n_pos > 0) fetch(0, ra);
+    if (n_pos > ST) fetch(ST, rb);
+    for (int i0 = 0; i0 < n_pos; i0 += 3 * ST) {
+      if (i0 + 2 * ST < n_pos) fetch(i0 + 2 * ST, rc);
+      reduce(i0, ra);
+      if (i0 + ST < n_pos) {
+        if (i0 + 3 * ST < n_pos) fetch(i0 + 3 * ST, ra);
+        reduce(i0 + ST, rb);
+      }
+      if (i0 + 2 * ST < n_pos) {
+        if (i0 + 4 * ST < n_pos) fetch(i0 + 4 * ST, rb);
+        reduce(i0 + 2 * ST, rc);
       }
     }
     // ---- combine the 4 slots of a wavefront: they share the running max ----
-    if constexpr (FUSED) __syncthreads();   // red aliases arrays the row resolution read
 #pragma unroll
     for (int g = 0; g < G; ++g)
 #pragma unroll
@@ -373,7 +537,6 @@ __global__ __launch_bounds__(ATT_THREADS) void k_attn_partial(const AttnArgs a) 
     }
 
     // ---- combine the 4 slots of a wavefront (lanes l16 + 16*k) ----
-    if constexpr (FUSED) __syncthreads();   // red aliases arrays the row resolution read
 #pragma unroll
     for (int g = 0; g < G; ++g) {
       const float mx = xor32(xor16(m[g], OpMax()), OpMax());
@@ -393,6 +556,7 @@ __global__ __launch_bounds__(ATT_THREADS) void k_attn_partial(const AttnArgs a) 
   __syncthreads();
   // ---- combine the 4 wavefronts: thread = (query head g, channel pair) ----
   T* out = static_cast<T*>(a.out);
+  float* part_hp = a.part + (int64_t)hp * a.n_split * G * PART_STRIDE;
   for (int e = tid; e < G * (D / 2); e += ATT_THREADS) {
     const int g = e / (D / 2), c2 = (e % (D / 2)) * 2;
     const float* r0 = red + (0 * G + g) * PART_STRIDE;
@@ -411,54 +575,71 @@ __global__ __launch_bounds__(ATT_THREADS) void k_attn_partial(const AttnArgs a) 
       store_out(o, a0 * inv);
       store_out(o + 1, a1 * inv);
     } else {
-      float* pr = a.part + (((int64_t)hp * a.n_split + split) * G + g) * PART_STRIDE;
-      if (c2 == 0) {
-        pr[0] = mx;
-        pr[1] = ls;
+      float* pr = part_hp + ((int64_t)split * G + g) * PART_STRIDE;
+      if (a.two_pass) {
+        if (c2 == 0) *reinterpret_cast<float2*>(pr) = make_float2(mx, ls);
+        *reinterpret_cast<float2*>(pr + 2 + c2) = make_float2(a0, a1);
+      } else {
+        if (c2 == 0) put_pair_agent(pr, mx, ls);
+        put_pair_agent(pr + 2 + c2, a0, a1);
       }
-      pr[2 + c2] = a0;
-      pr[3 + c2] = a1;
     }
+  }
+  if (a.n_split == 1 || a.two_pass) return;
+
+  // ---- ticket: the last workgroup of the head-problem to get here merges ----
+  // Every thread waits until its stores above have been acknowledged (they are
+  // agent-scope stores: performed where every XCD looks) before it passes the barrier;
+  // only then is the ticket drawn.
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+  if (tid == 0) {
+    // Idle state of a ticket word: TICKET_MAGIC in the upper 48 bits, count 0.  One
+    // fetch-add draws the ticket.  A word that does not carry the mark (memory this
+    // library has never used: the first launch on a fresh workspace) is taken over with
+    // a compare-and-swap loop instead; whoever added to it before the take-over adds
+    // itself again through the same loop, so every workgroup is counted exactly once.
+    unsigned long long* tk = a.tickets + hp;
+    unsigned long long old =
+        __hip_atomic_fetch_add(tk, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned long long now = old + 1;
+    if ((old >> 16) != TICKET_MAGIC) {
+      unsigned long long seen = now;
+      do {
+        now = (seen >> 16) == TICKET_MAGIC ? seen + 1 : ((TICKET_MAGIC << 16) | 1ull);
+      } while (!__hip_atomic_compare_exchange_strong(tk, &seen, now, __ATOMIC_RELAXED,
+                                                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    }
+    const int last = (int)(now & 0xFFFFull) == a.n_split;
+    // back to idle: ready for the next launch (or a replay of this one from a graph)
+    if (last) __hip_atomic_store(tk, TICKET_MAGIC << 16, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    s_last = last;
+  }
+  __syncthreads();
+  if (!s_last) return;
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  for (int e = tid; e < G * (D / 2); e += ATT_THREADS) {
+    const int g = e / (D / 2), c2 = (e % (D / 2)) * 2;
+    const float2 o2 = merge_splits(part_hp + (int64_t)g * PART_STRIDE, (int64_t)G * PART_STRIDE,
+                                   a.n_split, c2, PairAgent());
+    T* o = out + ((int64_t)s * a.Hq + h * G + g) * D + c2;
+    store_out(o, o2.x);
+    store_out(o + 1, o2.y);
   }
 }
 
-// out[hq] = sum_i acc_i 2^(m_i - M) / sum_i l_i 2^(m_i - M); the partials of up to
-// MERGE_BATCH splits are loaded together so that their latencies overlap.
-constexpr int MERGE_BATCH = 16;
+// Second pass of the two-pass form: the same merge, by a kernel of its own.
 template <typename T>
-__global__ __launch_bounds__(D) void k_attn_merge(const float* __restrict__ part, int n_split,
-                                                  int G, int Hq, int Hkv, T* __restrict__ out) {
+__global__ __launch_bounds__(D / 2) void k_attn_merge(const float* __restrict__ part, int n_split,
+                                                      int G, int Hq, int Hkv, T* __restrict__ out) {
   const int hq_lin = blockIdx.x;                        // s * Hq + hq
   const int s = hq_lin / Hq, hq = hq_lin % Hq;
-  const int hp = s * Hkv + hq / G, g = hq % G, t = threadIdx.x;
+  const int hp = s * Hkv + hq / G, g = hq % G, c2 = threadIdx.x * 2;
   const float* base = part + (((int64_t)hp * n_split) * G + g) * PART_STRIDE;
-  const int64_t stride = (int64_t)G * PART_STRIDE;
-  float M = NEG_BIG, ls = 0.f, acc = 0.f;
-  for (int i0 = 0; i0 < n_split; i0 += MERGE_BATCH) {
-    float mi[MERGE_BATCH], li[MERGE_BATCH], ai[MERGE_BATCH];
-#pragma unroll
-    for (int i = 0; i < MERGE_BATCH; ++i) {
-      const bool ok = i0 + i < n_split;
-      const float* p = base + (int64_t)(ok ? i0 + i : 0) * stride;
-      mi[i] = ok ? p[0] : NEG_BIG;
-      li[i] = ok ? p[1] : 0.f;
-      ai[i] = ok ? p[2 + t] : 0.f;
-    }
-    float mx = M;
-#pragma unroll
-    for (int i = 0; i < MERGE_BATCH; ++i) mx = fmaxf(mx, mi[i]);
-    const float corr = __builtin_amdgcn_exp2f(M - mx);
-    ls *= corr;
-    acc *= corr;
-    M = mx;
-#pragma unroll
-    for (int i = 0; i < MERGE_BATCH; ++i) {
-      const float f = __builtin_amdgcn_exp2f(mi[i] - mx);
-      ls += li[i] * f;
-      acc += ai[i] * f;
-    }
-  }
-  store_out(out + (int64_t)hq_lin * D + t, ls > 0.f ? acc / ls : 0.f);
+  const float2 o2 = merge_splits(base, (int64_t)G * PART_STRIDE, n_split, c2, PairPlain());
+  store_out(out + (int64_t)hq_lin * D + c2, o2.x);
+  store_out(out + (int64_t)hq_lin * D + c2 + 1, o2.y);
 }
 
 int attn_num_splits(const Dims& dm, int64_t max_total) {
@@ -475,32 +656,44 @@ int attn_num_splits(const Dims& dm, int64_t max_total) {
   return (int)n;
 }
 
-size_t attn_workspace_bytes(const Dims& dm, int64_t max_total) {
-  const int n_split = attn_num_splits(dm, max_total);
-  size_t b = (size_t)dm.HP * n_split * dm.G * PART_STRIDE * sizeof(float);
+static size_t partial_bytes(const Dims& dm, int n_split) {
+  const size_t b = (size_t)dm.HP * n_split * dm.G * PART_STRIDE * sizeof(float);
   return (b + 255) & ~(size_t)255;
 }
 
-template <typename T, bool FUSED>
-static hipError_t launch_attn_t(const Dims& dm, AttnArgs a, int64_t max_total, hipStream_t st) {
+size_t attn_workspace_bytes(const Dims& dm, int64_t max_total) {
+  // split partials, then one 64-bit ticket word per head-problem
+  const size_t t = ((size_t)dm.HP * sizeof(unsigned long long) + 255) & ~(size_t)255;
+  return partial_bytes(dm, attn_num_splits(dm, max_total)) + t;
+}
+
+template <typename T, int MODE, int CMAX>
+static hipError_t launch_attn_t(const Dims& dm, AttnArgs a, int64_t max_total, bool two_pass,
+                                hipStream_t st) {
   const int n_split = attn_num_splits(dm, max_total);
+  if (n_split > ATT_MAX_SPLITS) return hipErrorInvalidValue;
   int chunk = (int)((max_total + n_split - 1) / n_split);
   chunk = (chunk + ATT_STEP_TOKENS - 1) / ATT_STEP_TOKENS * ATT_STEP_TOKENS;
   if (chunk < ATT_STEP_TOKENS) chunk = ATT_STEP_TOKENS;
   if (chunk > ATT_MAX_CHUNK) return hipErrorInvalidValue;
   a.chunk = chunk;
   a.n_split = n_split;
-  const dim3 grid(n_split, dm.HP), block(ATT_THREADS);
+  a.two_pass = two_pass ? 1 : 0;
+  a.HP = dm.HP;
+  a.tickets = reinterpret_cast<unsigned long long*>(reinterpret_cast<char*>(a.part) +
+                                                    partial_bytes(dm, n_split));
+  const int hp_groups = (dm.HP + N_XCD - 1) / N_XCD;
+  const dim3 grid((unsigned)hp_groups * N_XCD * n_split), block(ATT_THREADS);
   switch (dm.G) {
-    case 1: hipLaunchKernelGGL((k_attn_partial<T, 1, FUSED>), grid, block, 0, st, a); break;
-    case 2: hipLaunchKernelGGL((k_attn_partial<T, 2, FUSED>), grid, block, 0, st, a); break;
-    case 4: hipLaunchKernelGGL((k_attn_partial<T, 4, FUSED>), grid, block, 0, st, a); break;
-    case 8: hipLaunchKernelGGL((k_attn_partial<T, 8, FUSED>), grid, block, 0, st, a); break;
+    case 1: hipLaunchKernelGGL((k_attn<T, 1, MODE, CMAX>), grid, block, 0, st, a); break;
+    case 2: hipLaunchKernelGGL((k_attn<T, 2, MODE, CMAX>), grid, block, 0, st, a); break;
+    case 4: hipLaunchKernelGGL((k_attn<T, 4, MODE, CMAX>), grid, block, 0, st, a); break;
+    case 8: hipLaunchKernelGGL((k_attn<T, 8, MODE, CMAX>), grid, block, 0, st, a); break;
     default: return hipErrorInvalidValue;
   }
-  if (n_split > 1)
-    hipLaunchKernelGGL(k_attn_merge<T>, dim3(dm.S * dm.Hq), dim3(D), 0, st, a.part, n_split, dm.G,
-                       dm.Hq, dm.Hkv, (T*)a.out);
+  if (n_split > 1 && two_pass)
+    hipLaunchKernelGGL(k_attn_merge<T>, dim3(dm.S * dm.Hq), dim3(D / 2), 0, st, a.part, n_split,
+                       dm.G, dm.Hq, dm.Hkv, (T*)a.out);
   return hipGetLastError();
 }
 
@@ -530,20 +723,56 @@ hipError_t launch_sparse_attn(const Dims& dm, const void* q, const void* K, cons
                               const int32_t* token_idx, const int32_t* n_tokens, int idx_stride,
                               int64_t max_total, int64_t n_sink, int64_t recent_begin,
                               int64_t recent_end, float softmax_scale, void* out, void* workspace,
-                              hipStream_t st) {
+                              bool two_pass, hipStream_t st) {
   const int n_recent = (int)(recent_end > recent_begin ? recent_end - recent_begin : 0);
   AttnArgs a = common_args(dm, q, K, V, idx_stride, (int)(max_total - n_sink - n_recent), n_sink,
                            recent_begin, recent_end, softmax_scale, out, workspace);
   a.token_idx = token_idx;
   a.n_tokens = n_tokens;
-  if (dm.dtype == CK_BF16) return launch_attn_t<bf16, false>(dm, a, max_total, st);
-  return launch_attn_t<float, false>(dm, a, max_total, st);
+  if (dm.dtype == CK_BF16)
+    return launch_attn_t<bf16, ATT_PLAIN, SELP_SMALL>(dm, a, max_total, two_pass, st);
+  return launch_attn_t<float, ATT_PLAIN, SELP_SMALL>(dm, a, max_total, two_pass, st);
+}
+
+hipError_t launch_decode_fused(const Dims& dm, const void* q, const void* K, const void* V,
+                               const void* centroids, const int32_t* sizes,
+                               const int32_t* offsets, const int32_t* sorted_idx, int n_clusters,
+                               int budget, uint32_t flags, int64_t n_sink, int64_t recent_begin,
+                               int64_t recent_end, float softmax_scale, float* scores,
+                               int32_t* sel_clusters, int32_t* n_sel_clusters,
+                               int32_t* n_sel_tokens, int32_t* token_idx, int idx_stride,
+                               int32_t* n_tokens, void* out, void* workspace, hipStream_t st) {
+  AttnArgs a = common_args(dm, q, K, V, idx_stride, budget, n_sink, recent_begin, recent_end,
+                           softmax_scale, out, workspace);
+  a.centroids = centroids;
+  a.scores = scores;
+  a.sizes = sizes;
+  a.offsets = offsets;
+  a.sorted_idx = sorted_idx;
+  a.sel_clusters = sel_clusters;
+  a.n_sel_clusters = n_sel_clusters;
+  a.n_sel_tokens = n_sel_tokens;
+  a.token_idx_out = token_idx;
+  a.n_tokens_out = n_tokens;
+  a.n_clusters = n_clusters;
+  a.budget = budget;
+  a.trim = (int)(flags & CK_SEL_TRIM_LAST);
+  const int64_t max_total = (int64_t)budget + n_sink + a.n_recent;
+  if (dm.dtype == CK_BF16 && n_clusters <= SELP_SMALL)  // one launch for the whole step
+    return launch_attn_t<bf16, ATT_FUSED_SCORE, SELP_SMALL>(dm, a, max_total, false, st);
+  const hipError_t e = launch_score(dm, q, centroids, n_clusters, scores, st);
+  if (e != hipSuccess) return e;
+  if (dm.dtype == CK_BF16)
+    return launch_attn_t<bf16, ATT_FUSED, CK_MAX_CLUSTERS>(dm, a, max_total, false, st);
+  if (n_clusters <= SELP_SMALL)
+    return launch_attn_t<float, ATT_FUSED, SELP_SMALL>(dm, a, max_total, false, st);
+  return launch_attn_t<float, ATT_FUSED, CK_MAX_CLUSTERS>(dm, a, max_total, false, st);
 }
 
 // ---- library-owned scratch for callers that cannot allocate ----
-// The split partials of one attention call, in device memory that exists from the
-// moment the code object is loaded: every GPU the library runs on holds its own
-// copy of the array until the process ends.  Host code never passes the array's
+// The split partials and tickets of one attention call, in device memory that exists
+// from the moment the code object is loaded: every GPU the library runs on holds its
+// own copy of the array until the process ends.  Host code never passes the array's
 // name anywhere; it asks the runtime once per device for the array's address on
 // that device and uses that pointer from then on.
 static __device__ __align__(256) unsigned char scratch[CK_STATIC_SCRATCH_BYTES];
@@ -567,35 +796,6 @@ hipError_t attn_static_scratch(void** ptr) {
   }
   *ptr = g_scratch_ptr[dev];
   return hipSuccess;
-}
-
-hipError_t launch_decode_fused(const Dims& dm, const void* q, const void* K, const void* V,
-                               const void* centroids, const int32_t* sizes,
-                               const int32_t* offsets, const int32_t* sorted_idx, int n_clusters,
-                               int budget, uint32_t flags, int64_t n_sink, int64_t recent_begin,
-                               int64_t recent_end, float softmax_scale, float* scores,
-                               int32_t* sel_clusters, int32_t* n_sel_clusters,
-                               int32_t* n_sel_tokens, int32_t* token_idx, int idx_stride,
-                               int32_t* n_tokens, void* out, void* workspace, hipStream_t st) {
-  hipError_t e = launch_score(dm, q, centroids, n_clusters, scores, st);
-  if (e != hipSuccess) return e;
-  AttnArgs a = common_args(dm, q, K, V, idx_stride, budget, n_sink, recent_begin, recent_end,
-                           softmax_scale, out, workspace);
-  a.scores = scores;
-  a.sizes = sizes;
-  a.offsets = offsets;
-  a.sorted_idx = sorted_idx;
-  a.sel_clusters = sel_clusters;
-  a.n_sel_clusters = n_sel_clusters;
-  a.n_sel_tokens = n_sel_tokens;
-  a.token_idx_out = token_idx;
-  a.n_tokens_out = n_tokens;
-  a.n_clusters = n_clusters;
-  a.budget = budget;
-  a.trim = (int)(flags & CK_SEL_TRIM_LAST);
-  const int64_t max_total = (int64_t)budget + n_sink + a.n_recent;
-  if (dm.dtype == CK_BF16) return launch_attn_t<bf16, true>(dm, a, max_total, st);
-  return launch_attn_t<float, true>(dm, a, max_total, st);
 }
 
 }  // namespace ck
