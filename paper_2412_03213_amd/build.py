@@ -18,7 +18,7 @@ INCLUDE = os.path.join(ROOT, "include")
 OBJ_DIR = os.path.join(ROOT, "_build")
 LIB = os.path.join(PKG, "libclusterkv.so")
 
-SOURCES = ["api.hip", "kmeans_assign.hip", "kmeans_update.hip", "kmeans_small.hip", "select_gather.hip",
+SOURCES = ["api.hip", "kmeans_assign.hip", "kmeans_assign_stream.hip", "kmeans_update.hip", "kmeans_small.hip", "select_gather.hip",
            "sparse_attn.hip", "evaluate.hip", "cluster_cache.hip",
            "probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -26,6 +26,11 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
          # packed-FP32 instruction selection is kept off for every device function
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", INCLUDE, "-I", CSRC]
+
+
+# per-file additions: keep MFMA accumulators in vector registers where the kernel reads
+# them with vector instructions and has other data (MFMA-only operands) for the AGPRs
+EXTRA_FLAGS = {"kmeans_assign_stream.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
 def _newer(a: str, b: str) -> bool:
@@ -43,7 +48,7 @@ def build(force: bool = False, verbose: bool = True) -> str:
         o = os.path.join(OBJ_DIR, src.replace(".hip", ".o"))
         objs.append(o)
         if force or _newer(s, o) or any(_newer(h, o) for h in headers):
-            jobs.append([HIPCC, *FLAGS, "-c", s, "-o", o])
+            jobs.append([HIPCC, *FLAGS, *EXTRA_FLAGS.get(src, []), "-c", s, "-o", o])
 
     def run(cmd):
         if verbose:

@@ -175,6 +175,12 @@ int assign_tile_tokens(const Dims& dm, int64_t tok_count);
 hipError_t launch_assign(const Dims& dm, const bf16* K, int64_t tok_begin, int64_t tok_count,
                          const bf16* mu_hat, int c_begin, int c_count, int32_t* labels,
                          float* best_sim, int32_t* chunk_hist, const KmCtl& ctl, hipStream_t st);
+// streaming form for small tables (whole table in LDS); chunk size 512 tokens as above
+bool assign_stream_fits(int c_count);
+hipError_t launch_assign_stream(const Dims& dm, const bf16* K, int64_t tok_begin,
+                                int64_t tok_count, const bf16* mu_hat, int c_begin, int c_count,
+                                int32_t* labels, float* best_sim, int32_t* chunk_hist,
+                                const KmCtl& ctl, int n_cu, hipStream_t st);
 // have_hist: chunk_hist already holds the histograms (written by launch_assign)
 hipError_t launch_metadata(const Dims& dm, const int32_t* labels, int64_t tok_begin,
                            int64_t tok_count, int c_begin, int c_count, int32_t* sizes,

@@ -306,6 +306,9 @@ hipError_t launch_assign(const Dims& dm, const bf16* K, int64_t tok_begin, int64
     // two independent four-wavefront workgroups per CU overlap one's key load and
     // epilogue with the other's tile loop (measured: +8 % at 64 head-problems, C = 400).
     const int n_cu = compute_units();
+    if (assign_stream_fits(c_count))
+      return launch_assign_stream(dm, K, tok_begin, tok_count, mu_hat, c_begin, c_count, labels,
+                                  best_sim, chunk_hist, ctl, n_cu, st);
     const int64_t wg8 = (tok_count + 1023) / 1024 * dm.HP;
     if (wg8 > n_cu && c_count < 1024) {
       launch_assign_variant<4, 4, 2, false>(dm, K, tok_begin, tok_count, mu_hat, c_begin, c_count,
