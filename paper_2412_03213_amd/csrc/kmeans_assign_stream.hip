@@ -27,7 +27,7 @@ constexpr int LDS_ROW = D + 8;             // bf16 elements per LDS row: 272 B, 
 // its last MFMA has been issued.  Two such wavefronts per SIMD cover each other's
 // remaining stalls (measured on a register-only replica: 79 % of the MFMA peak with
 // this mix of MFMA, vector and LDS instructions, against 65 % with one wavefront).
-// Block b of the eight wavefronts together is one 512-token chunk of the counting sort.
+// Eight consecutive tasks of 64 tokens are one 512-token chunk of the counting sort.
 constexpr int ST_WAVES = 8;
 constexpr int ST_NKB = 2;                               // 64 keys per wavefront and block
 constexpr int ST_CHUNK = ST_WAVES * ST_NKB * 32;        // 512 tokens per block of a workgroup
@@ -45,7 +45,7 @@ __global__ __launch_bounds__(ST_WAVES * 64, 2) void k_assign_stream(
   __shared__ __attribute__((aligned(16))) bf16 table[ST_MAX_TILES * 32 * LDS_ROW];
   __shared__ __attribute__((aligned(16))) float lds_bias[HAS_BIAS ? ST_MAX_TILES * 32 : 4];
   __shared__ int hist[ST_HIST_INTS];
-  __shared__ int s_changed;
+  __shared__ int s_changed, s_next_task;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 31, half = lane >> 5;
@@ -56,13 +56,12 @@ __global__ __launch_bounds__(ST_WAVES * 64, 2) void k_assign_stream(
   const int n_tiles = (c_count + 31) / 32;
   const int64_t wg_tok0 = (int64_t)blockIdx.x * blocks * ST_CHUNK;
 
-  // keys of block b of this wavefront, in B-operand layout; key block 0 is requested
-  // first: the tile loop starts with it
+  // keys of task b (64 consecutive tokens of this workgroup's range), in B-operand layout
   auto load_keys = [&](int b, bf16x8 (&bk)[NKB][8]) {
     const bf16* rows[NKB];
 #pragma unroll
     for (int kb = 0; kb < NKB; ++kb) {
-      int64_t t = wg_tok0 + (int64_t)b * ST_CHUNK + wave * (NKB * 32) + kb * 32 + col;
+      int64_t t = wg_tok0 + (int64_t)b * (NKB * 32) + kb * 32 + col;
       if (t >= tok_count) t = tok_count - 1;            // clamp: result is discarded
       rows[kb] = Khp + (tok_begin + t) * D + half * 8;
     }
@@ -99,14 +98,17 @@ __global__ __launch_bounds__(ST_WAVES * 64, 2) void k_assign_stream(
   }
   // the first keys are requested after the table: loads come back in the order they were
   // issued, and the table (mostly out of L2) must not wait behind 32 MB of keys from HBM
-  load_keys(0, ka);
+  load_keys(wave, ka);
   if constexpr (HAS_BIAS) {
     for (int c = tid; c < n_tiles * 32; c += THREADS)
       lds_bias[c] = c < c_count ? ctl.bias[(int64_t)hp * ctl.bias_stride + c] : 0.f;
   }
   if (chunk_hist)
     for (int c = tid; c < blocks * c_count; c += THREADS) hist[c] = 0;
-  if (tid == 0) s_changed = 0;
+  if (tid == 0) {
+    s_changed = 0;
+    s_next_task = ST_WAVES;                             // tasks 0..7 are the wavefronts' first ones
+  }
   __syncthreads();
 
   int diff = 0;
@@ -114,7 +116,7 @@ __global__ __launch_bounds__(ST_WAVES * 64, 2) void k_assign_stream(
 
   // One block of 128 keys against every centroid tile, then its labels.
   auto process = [&](int b, const bf16x8 (&bk)[NKB][8]) {
-    const int64_t wave_tok0 = wg_tok0 + (int64_t)b * ST_CHUNK + wave * (NKB * 32);
+    const int64_t wave_tok0 = wg_tok0 + (int64_t)b * (NKB * 32);
     if (wave_tok0 >= tok_count) return;                 // wave-uniform: nothing of this block exists
     float bestp[NKB];
     int btile[NKB];
@@ -209,18 +211,34 @@ __global__ __launch_bounds__(ST_WAVES * 64, 2) void k_assign_stream(
         if (ctl.changed) diff += (ctl.first || labels[o] != c_begin + bidx) ? 1 : 0;
         labels[o] = c_begin + bidx;
         if (best_sim) best_sim[o] = __uint_as_float(__float_as_uint(best) & 0xFFFFFFF0u);
-        if (chunk_hist) atomicAdd(&hist[b * c_count + bidx], 1);   // integer counts: any order
+        if (chunk_hist) atomicAdd(&hist[(b / ST_WAVES) * c_count + bidx], 1);   // integer counts: any order
       }
     }
   };
 
-  for (int b = 0; b < blocks; b += 2) {
-    if (b + 1 < blocks) load_keys(b + 1, kb2);
-    process(b, ka);
-    if (b + 1 < blocks) {
-      if (b + 2 < blocks) load_keys(b + 2, ka);
-      process(b + 1, kb2);
-    }
+  // A workgroup's range is cut into tasks of 64 tokens (8 per 512-token chunk).  Every
+  // wavefront starts with the task of its own number and then takes the next free one
+  // from a shared counter, always one task ahead so that the keys can be requested a
+  // whole task early.  Two wavefronts share a SIMD and the hardware does not split it
+  // evenly between them; with a fixed share the slower one would finish alone, at the
+  // speed of one wavefront.
+  const int n_tasks = blocks * ST_WAVES;
+  auto grab = [&]() {
+    int t = 0;
+    if (lane == 0) t = atomicAdd(&s_next_task, 1);
+    return __builtin_amdgcn_readfirstlane(t);
+  };
+  int cur = wave;
+  while (cur < n_tasks) {
+    int nxt = grab();
+    if (nxt < n_tasks) load_keys(nxt, kb2);
+    process(cur, ka);
+    cur = nxt;
+    if (cur >= n_tasks) break;
+    nxt = grab();
+    if (nxt < n_tasks) load_keys(nxt, ka);
+    process(cur, kb2);
+    cur = nxt;
   }
 
   if (ctl.changed) {
