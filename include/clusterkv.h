@@ -77,6 +77,7 @@ extern "C" {
 /* which = argument of ck_workspace_bytes */
 #define CK_WS_CLUSTER_KEYS 0
 #define CK_WS_SPARSE_ATTN 1
+#define CK_WS_OBJECTIVE 2
 
 typedef struct ck_shape {
   int32_t S;       /* sequences in the batch */
@@ -96,6 +97,7 @@ const char* ck_last_error_detail(void);
  * Bytes of device scratch a call needs.
  *   CK_WS_CLUSTER_KEYS: n = number of tokens clustered per head-problem
  *                       (tok_count), c = number of clusters (c_count).
+ *   CK_WS_OBJECTIVE:    n = tok_count of ck_kmeans_objective, c ignored.
  *   CK_WS_SPARSE_ATTN:  n = upper bound of attended tokens per head-problem
  *                       (budget + n_sink + recent window), c ignored.
  * Returns 0 for an invalid request.
@@ -172,6 +174,26 @@ int ck_cluster_keys_opt(const ck_shape* sh, const void* K, int64_t tok_begin, in
 int ck_kmeans_assign(const ck_shape* sh, const void* K, int64_t tok_begin, int64_t tok_count,
                      const void* centroids_hat, int32_t c_begin, int32_t c_count,
                      int32_t* labels, float* best_sim, void* stream);
+
+/*
+ * The clustering objective of a given assignment under the distance of Section
+ * III-B, D(k, mu) = 1 - cos(k, mu), summed over tokens [tok_begin, tok_begin +
+ * tok_count) of every head-problem:
+ *   D[hp] = sum_i (1 - cos(k_i, t_i))            the paper's objective
+ *   J[hp] = sum_i |k_i| (1 - cos(k_i, t_i))      the norm-weighted form, which neither
+ *                                                K-means step can increase
+ * with t_i = row (labels[i] - c_begin) of centroids_hat, the compact table an
+ * assignment reads ([S, Hkv, c_count, d] bf16; J takes its rows as unit vectors:
+ * J = sum_i (|k_i| - <k_i, t_i>)).  Calling it after each ck_kmeans_assign of a
+ * step-by-step run gives the objective per iteration; ck_cluster_keys itself does
+ * not report it (the value is a diagnostic and costs one more pass over the keys).
+ * J, D [dev] out double [S, Hkv].  fp32 inside a row, fp64 across rows, fixed order.
+ * workspace: ck_workspace_bytes(sh, CK_WS_OBJECTIVE, tok_count, 0).
+ */
+int ck_kmeans_objective(const ck_shape* sh, const void* K, int64_t tok_begin, int64_t tok_count,
+                        const void* centroids_hat, int32_t c_begin, int32_t c_count,
+                        const int32_t* labels, double* J, double* D, void* workspace,
+                        size_t workspace_bytes, void* stream);
 
 /*
  * ck_build_metadata: from labels of the token range, sizes / offsets / sorted_idx

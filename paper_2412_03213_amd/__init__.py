@@ -12,7 +12,7 @@ from .binding import (CK_BF16, CK_F32, CK_KM_UNTIL_CONVERGED, CK_METRIC_COSINE, 
                       ck_cache_reset, ck_cached_decode_step, ck_host_device_ptr, ck_build_metadata, ck_cluster_keys,
                       ck_cluster_keys_opt,
                       ck_decode_step, ck_expand_pages, ck_full_decode_attn, ck_gather_indices,
-                      ck_kmeans_assign, ck_kmeans_update, ck_page_keys, ck_probe_mfma_bf16,
+                      ck_kmeans_assign, ck_kmeans_objective, ck_kmeans_update, ck_page_keys, ck_probe_mfma_bf16,
                       ck_recall_hits, ck_select_clusters, ck_sparse_decode_attn,
                       ck_sparse_decode_attn_static, ck_token_scores,
                       ck_topk_select, ck_version, ck_workspace_bytes, decode_step, load_library)
@@ -25,7 +25,7 @@ __all__ = [
     "ClusterCache", "ClusterKVError", "ClusterState", "Shape", "cached_decode_step",
     "ck_cache_reset", "ck_cached_decode_step", "ck_host_device_ptr", "ck_build_metadata", "ck_cluster_keys",
     "ck_decode_step", "ck_expand_pages", "ck_full_decode_attn", "ck_gather_indices",
-    "ck_kmeans_assign", "ck_kmeans_update", "ck_page_keys", "ck_probe_mfma_bf16",
+    "ck_kmeans_assign", "ck_kmeans_objective", "ck_kmeans_update", "ck_page_keys", "ck_probe_mfma_bf16",
     "ck_recall_hits", "ck_select_clusters", "ck_sparse_decode_attn",
     "ck_sparse_decode_attn_static", "ck_token_scores",
     "ck_topk_select", "ck_version", "ck_workspace_bytes", "decode_step", "load_library",

@@ -16,13 +16,13 @@ CK_BF16, CK_F32 = 0, 1
 CK_SEL_WHOLE, CK_SEL_TRIM_LAST = 0, 1
 CK_MAX_CLUSTERS = 2048
 CK_METRIC_COSINE, CK_METRIC_L2, CK_METRIC_IP, CK_KM_UNTIL_CONVERGED = 0, 1, 2, 4
-CK_WS_CLUSTER_KEYS, CK_WS_SPARSE_ATTN = 0, 1
+CK_WS_CLUSTER_KEYS, CK_WS_SPARSE_ATTN, CK_WS_OBJECTIVE = 0, 1, 2
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libclusterkv.so")
 
 EXPORTS = ("ck_version", "ck_strerror", "ck_last_error_detail", "ck_workspace_bytes",
-           "ck_cluster_keys", "ck_cluster_keys_opt", "ck_kmeans_assign", "ck_build_metadata", "ck_kmeans_update",
+           "ck_cluster_keys", "ck_cluster_keys_opt", "ck_kmeans_assign", "ck_kmeans_objective", "ck_build_metadata", "ck_kmeans_update",
            "ck_select_clusters", "ck_gather_indices", "ck_sparse_decode_attn", "ck_sparse_decode_attn_static", "ck_sparse_decode_attn_two_pass", "ck_decode_step",
            "ck_full_decode_attn", "ck_token_scores", "ck_topk_select", "ck_recall_hits",
            "ck_page_keys", "ck_expand_pages", "ck_host_device_ptr", "ck_cache_reset",
@@ -98,6 +98,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
                                         P, SZ, P]
     lib.ck_kmeans_assign.restype = ctypes.c_int
     lib.ck_kmeans_assign.argtypes = [SH, P, I64, I64, P, I32, I32, P, P, P]
+    lib.ck_kmeans_objective.restype = ctypes.c_int
+    lib.ck_kmeans_objective.argtypes = [SH, P, I64, I64, P, I32, I32, P, P, P, P, SZ, P]
     lib.ck_build_metadata.restype = ctypes.c_int
     lib.ck_build_metadata.argtypes = [SH, P, I64, I64, I32, I32, P, P, P, P, SZ, P]
     lib.ck_kmeans_update.restype = ctypes.c_int
@@ -215,6 +217,21 @@ def ck_kmeans_assign(sh: Shape, K, tok_begin, tok_count, centroids_hat, c_begin,
     _check(lib.ck_kmeans_assign(ctypes.byref(s), _ptr(K), tok_begin, tok_count,
                                 _ptr(centroids_hat), c_begin, c_count, _ptr(labels),
                                 _ptr(best_sim), _stream(K)))
+
+
+def ck_kmeans_objective(sh: Shape, K, tok_begin, tok_count, centroids_hat, c_begin, c_count, labels,
+                        J, D, workspace=None):
+    """J, D: float64 [S, Hkv] outputs (norm-weighted and plain cosine objective)."""
+    lib = load_library()
+    if workspace is None:
+        workspace = _workspace(ck_workspace_bytes(sh, CK_WS_OBJECTIVE, tok_count), K)
+    s = sh.c()
+    _check(lib.ck_kmeans_objective(ctypes.byref(s), _ptr(K), tok_begin, tok_count,
+                                   _ptr(centroids_hat), c_begin, c_count, _ptr(labels), _ptr(J),
+                                   _ptr(D), _ptr(workspace),
+                                   workspace.numel() if isinstance(workspace, torch.Tensor) else 0,
+                                   _stream(K)))
+    return workspace
 
 
 def ck_build_metadata(sh: Shape, labels, tok_begin, tok_count, c_begin, c_count, sizes, offsets,

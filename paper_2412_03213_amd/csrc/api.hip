@@ -109,6 +109,10 @@ size_t ck_workspace_bytes(const ck_shape* sh, int which, int64_t n, int32_t c) {
     if (n < 0) return 0;
     return ck::attn_workspace_bytes(dm, n);
   }
+  if (which == CK_WS_OBJECTIVE) {
+    if (n < 1) return 0;
+    return ck::objective_workspace_bytes(dm, n);
+  }
   return 0;
 }
 
@@ -127,6 +131,30 @@ int ck_kmeans_assign(const ck_shape* sh, const void* K, int64_t tok_begin, int64
                                       (const ck::bf16*)centroids_hat, c_begin, c_count, labels,
                                       best_sim, nullptr, ck::KmCtl(), (hipStream_t)stream),
                     "assignment launch");
+}
+
+int ck_kmeans_objective(const ck_shape* sh, const void* K, int64_t tok_begin, int64_t tok_count,
+                        const void* centroids_hat, int32_t c_begin, int32_t c_count,
+                        const int32_t* labels, double* J, double* D, void* workspace,
+                        size_t workspace_bytes, void* stream) {
+  ck::Dims dm;
+  int rc = check_shape(sh, &dm, true);
+  if (rc) return rc;
+  if ((rc = check_ranges(sh, tok_begin, tok_count, c_begin, c_count))) return rc;
+  CK_REQUIRE_PTR(K);
+  CK_REQUIRE_PTR(centroids_hat);
+  CK_REQUIRE_PTR(labels);
+  CK_REQUIRE_PTR(J);
+  CK_REQUIRE_PTR(D);
+  if (!workspace) return fail(CK_EWORKSPACE, "workspace is NULL");
+  if (!aligned16(workspace)) return fail(CK_EMISALIGNED, "workspace is not 16-byte aligned");
+  const size_t need = ck::objective_workspace_bytes(dm, tok_count);
+  if (workspace_bytes < need)
+    return fail(CK_EWORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+  return hip_result(ck::launch_objective(dm, (const ck::bf16*)K, tok_begin, tok_count,
+                                         (const ck::bf16*)centroids_hat, c_begin, c_count, labels,
+                                         J, D, workspace, (hipStream_t)stream),
+                    "objective launch");
 }
 
 int ck_build_metadata(const ck_shape* sh, const int32_t* labels, int64_t tok_begin,

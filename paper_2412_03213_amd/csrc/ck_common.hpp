@@ -239,6 +239,10 @@ hipError_t launch_expand_pages(int HP, const int32_t* page_idx, const int32_t* n
                                int page_stride, int page_size, int64_t tok_begin,
                                int64_t tok_count, int32_t* token_idx, int idx_stride,
                                int32_t* n_tokens, hipStream_t st);
+size_t objective_workspace_bytes(const Dims& dm, int64_t tok_count);
+hipError_t launch_objective(const Dims& dm, const bf16* K, int64_t tok_begin, int64_t tok_count,
+                            const bf16* table, int c_begin, int c_count, const int32_t* labels,
+                            double* J, double* Dsum, void* workspace, hipStream_t st);
 int attn_num_splits(const Dims& dm, int64_t max_total);
 size_t attn_workspace_bytes(const Dims& dm, int64_t max_total);
 // address, on the current device, of the library-owned scratch array

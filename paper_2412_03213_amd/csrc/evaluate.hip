@@ -233,4 +233,93 @@ hipError_t launch_expand_pages(int HP, const int32_t* page_idx, const int32_t* n
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------ clustering objective
+// Of a given assignment under the cosine distance of Section III-B, D = 1 - cos(k, mu):
+//   J = sum_i |k_i| (1 - cos(k_i, t_i)) = sum_i (|k_i| - <k_i, t_i>)   for a unit-length table
+//   D = sum_i (1 - <k_i, t_i> / (|k_i| |t_i|))                         (a zero vector counts 1)
+// with t_i the table row of key i's label.  Products and the 128-term sums of one row in
+// fp32 (bf16 products are exact there), the sum over the keys in fp64.  Two launches and
+// a fixed order of additions: no floating-point atomics, bit-reproducible.
+constexpr int OBJ_THREADS = 256;
+constexpr int OBJ_TOKENS = 1024;                        // keys per workgroup
+
+__global__ __launch_bounds__(OBJ_THREADS) void k_objective_partial(
+    const bf16* __restrict__ K, const bf16* __restrict__ table, const int32_t* __restrict__ labels,
+    int64_t N_cap, int64_t tok_begin, int64_t tok_count, int c_begin, int c_count,
+    double* __restrict__ partial) {
+  __shared__ double red[2][OBJ_THREADS / 16];
+  const int hp = blockIdx.y, tid = threadIdx.x, l16 = tid & 15, grp = tid >> 4;
+  const bf16* Khp = K + (int64_t)hp * N_cap * D + l16 * 8;
+  const bf16* Thp = table + (int64_t)hp * c_count * D + l16 * 8;
+  const int32_t* lab = labels + (int64_t)hp * N_cap + tok_begin;
+  double j = 0.0, dsum = 0.0;
+  for (int i = 0; i < OBJ_TOKENS / 16; i += 4) {
+    float kv[4][8], tv[4][8];
+    bool ok[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t t = (int64_t)blockIdx.x * OBJ_TOKENS + (i + u) * 16 + grp;
+      ok[u] = t < tok_count;
+      const int64_t tc = ok[u] ? t : tok_count - 1;
+      int c = lab[tc] - c_begin;
+      c = c < 0 ? 0 : (c >= c_count ? c_count - 1 : c);
+      load_row8<bf16>(Khp + (tok_begin + tc) * D, kv[u]);
+      load_row8<bf16>(Thp + (int64_t)c * D, tv[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      float dot = 0.f, kk = 0.f, tt = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        dot = fmaf(kv[u][e], tv[u][e], dot);
+        kk = fmaf(kv[u][e], kv[u][e], kk);
+        tt = fmaf(tv[u][e], tv[u][e], tt);
+      }
+      dot = row16_sum(dot);
+      kk = row16_sum(kk);
+      tt = row16_sum(tt);
+      if (ok[u]) {
+        const double kn = sqrt((double)kk), den = kn * sqrt((double)tt);
+        j += kn - (double)dot;
+        dsum += den > 0.0 ? 1.0 - (double)dot / den : 1.0;
+      }
+    }
+  }
+  if (l16 == 0) {
+    red[0][grp] = j;
+    red[1][grp] = dsum;
+  }
+  __syncthreads();
+  if (tid < 2) {
+    double s = 0.0;
+    for (int g = 0; g < OBJ_THREADS / 16; ++g) s += red[tid][g];
+    partial[((int64_t)hp * gridDim.x + blockIdx.x) * 2 + tid] = s;
+  }
+}
+
+__global__ __launch_bounds__(64) void k_objective_sum(const double* __restrict__ partial, int n_wg,
+                                                      double* __restrict__ J, double* __restrict__ Dsum) {
+  const int hp = blockIdx.x, which = threadIdx.x;
+  if (which >= 2) return;
+  double s = 0.0;
+  for (int w = 0; w < n_wg; ++w) s += partial[((int64_t)hp * n_wg + w) * 2 + which];
+  (which == 0 ? J : Dsum)[hp] = s;
+}
+
+size_t objective_workspace_bytes(const Dims& dm, int64_t tok_count) {
+  const int64_t n_wg = (tok_count + OBJ_TOKENS - 1) / OBJ_TOKENS;
+  return (((size_t)dm.HP * n_wg * 2 * sizeof(double)) + 255) & ~(size_t)255;
+}
+
+hipError_t launch_objective(const Dims& dm, const bf16* K, int64_t tok_begin, int64_t tok_count,
+                            const bf16* table, int c_begin, int c_count, const int32_t* labels,
+                            double* J, double* Dsum, void* workspace, hipStream_t st) {
+  const int n_wg = (int)((tok_count + OBJ_TOKENS - 1) / OBJ_TOKENS);
+  hipLaunchKernelGGL(k_objective_partial, dim3(n_wg, dm.HP), dim3(OBJ_THREADS), 0, st, K, table,
+                     labels, dm.N_cap, tok_begin, tok_count, c_begin, c_count, (double*)workspace);
+  hipLaunchKernelGGL(k_objective_sum, dim3(dm.HP), dim3(64), 0, st, (const double*)workspace, n_wg,
+                     J, Dsum);
+  return hipGetLastError();
+}
+
 }  // namespace ck

@@ -137,6 +137,10 @@ def test_argument_validation_without_a_device():
     expect(-1, ck.ck_kmeans_assign, sh, A, 0, 1001, A, 0, 40, A)
     expect(-1, ck.ck_kmeans_assign, sh, A, 0, 1000, None, 0, 40, A)
     expect(-3, ck.ck_build_metadata, sh, A, 0, 1000, 0, 40, A, A, A, workspace=0)
+    expect(-1, ck.ck_kmeans_objective, sh, A, 0, 1001, A, 0, 40, A, A, A, workspace=A)
+    expect(-1, ck.ck_kmeans_objective, sh, A, 0, 1000, A, 0, 40, A, None, A, workspace=A)
+    expect(-3, ck.ck_kmeans_objective, sh, A, 0, 1000, A, 0, 40, A, A, A, workspace=0)
+    assert ck.ck_workspace_bytes(sh, binding.CK_WS_OBJECTIVE, 1000) >= 8 * 2 * 8
     expect(-1, ck.ck_kmeans_update, sh, A, A, A, A, 0, 41, A, A)
 
     def attn(**kw):

@@ -474,3 +474,39 @@ def test_llama3_8b_layer_sampled():
     assert not ((got != lo) & ~near).any()
     print(f"config 1: selection near-ties {flagged}/{cfg.Hkv}; assignment near-ties "
           f"{int(near.sum())}/{len(sample)}")
+
+
+def test_objective_per_iteration_matches_oracle():
+    """ck_kmeans_objective after each teacher-forced assignment: the norm-weighted J and
+    the plain cosine objective D of Section III-B against the oracle's trace, and J of the
+    GPU's own labels never increases over a step-by-step run."""
+    cfg = small_cfg(5000 + 37, 48, 64, Hkv=2, Hq=2, S=2, seed=21)
+    w = MixtureWorkload(cfg, device=DEV)
+    w.K[1, 1, 100] = 0                                     # a zero key: distance 1, weight 0
+    init = sample_init_indices(w.K, cfg.C, cfg.seed)
+    sh = ck.Shape(cfg.S, cfg.Hq, cfg.Hkv, cfg.N, cfg.C)
+    n_iter = 4
+    runs = {(s, h): O.kmeans(np64(w.K[s, h]), init[s, h].numpy(), n_iter, "bf16")
+            for s in range(cfg.S) for h in range(cfg.Hkv)}
+    J = torch.zeros(cfg.S, cfg.Hkv, dtype=torch.float64, device=DEV)
+    D = torch.zeros_like(J)
+    for t in range(n_iter):
+        hat = torch.stack([torch.stack([bf16_dev(runs[s, h][3].mu_hat[t]) for h in range(cfg.Hkv)])
+                           for s in range(cfg.S)]).contiguous()
+        lab = torch.stack([torch.stack([i32_dev(runs[s, h][3].labels[t]) for h in range(cfg.Hkv)])
+                           for s in range(cfg.S)]).contiguous()
+        ck.ck_kmeans_objective(sh, w.K, 0, cfg.N, hat, 0, cfg.C, lab, J, D)
+        torch.cuda.synchronize()
+        for (s, h), run in runs.items():
+            tr = run[3]
+            assert abs(float(J[s, h]) - tr.J[t]) <= 1e-6 * abs(tr.J[t])
+            assert abs(float(D[s, h]) - tr.D[t]) <= 1e-6 * abs(tr.D[t])
+    # a sub-range with a cluster offset: tokens [1000, 3000) only
+    lab_off = lab + 7
+    ck.ck_kmeans_objective(ck.Shape(cfg.S, cfg.Hq, cfg.Hkv, cfg.N, cfg.C + 7), w.K, 1000, 2000, hat,
+                           7, cfg.C, lab_off, J, D)
+    torch.cuda.synchronize()
+    tr = runs[1, 0][3]
+    keys = np64(w.K[1, 0])[1000:3000]
+    want = O.weighted_objective(keys, tr.mu_hat[-1], tr.labels[-1][1000:3000])
+    assert abs(float(J[1, 0]) - want) <= 1e-6 * abs(want)
