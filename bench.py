@@ -296,18 +296,27 @@ def graph_ms(fn, reps, per_graph=1):
 
 def measured_peaks(dev):
     """What the chip sustains in the simplest possible kernels: a register-only bf16
-    MFMA loop (constant operands, so it runs at the full clock) and a device copy."""
+    MFMA loop, once with constant operands and once with random ones (the clock the chip
+    holds under matrix load depends on how many operand bits toggle: the random-operand
+    figure is the one that bounds a kernel working on real keys), and a device copy."""
     import torch
     import paper_2412_03213_amd as ck
     sink = torch.zeros(4, device=dev)
-    ck.ck_probe_mfma_bf16(1024, 200, sink)
-    torch.cuda.synchronize()
+    clocks = torch.zeros(2, dtype=torch.int64, device=dev)
+    g = torch.Generator(device=dev).manual_seed(11)
+    rnd = torch.randn(64 * 16 * 8, generator=g, device=dev).to(torch.bfloat16).contiguous()
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    a.record()
-    fl = ck.ck_probe_mfma_bf16(1024, 4000, sink)
-    b.record()
-    b.synchronize()
-    mfma = fl / (a.elapsed_time(b) * 1e-3) / 1e12
+    out = {}
+    for tag, operands in (("constant_operands", None), ("random_operands", rnd)):
+        ck.ck_probe_mfma_bf16(1024, 200, sink, operands, clocks)
+        torch.cuda.synchronize()
+        a.record()
+        fl = ck.ck_probe_mfma_bf16(1024, 4000, sink, operands, clocks)
+        b.record()
+        b.synchronize()
+        cyc, tick = (int(x) for x in clocks.cpu())
+        out["mfma_bf16_TFLOPs_register_loop_" + tag] = fl / (a.elapsed_time(b) * 1e-3) / 1e12
+        out["shader_MHz_in_loop_" + tag] = cyc / max(tick, 1) * 100.0
     src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
     dst = torch.empty_like(src)
     dst.copy_(src)
@@ -317,10 +326,12 @@ def measured_peaks(dev):
         dst.copy_(src)
     b.record()
     b.synchronize()
-    copy = 5 * 2 * src.numel() / (a.elapsed_time(b) * 1e-3) / 1e9
-    return {"mfma_bf16_TFLOPs_register_loop": mfma, "copy_GBps_read_plus_write": copy,
-            "note": "register-only MFMA loop (constant operands) and a 1 GiB device copy: what "
-                    "the simplest possible kernels sustain on this chip"}
+    out["copy_GBps_read_plus_write"] = 5 * 2 * src.numel() / (a.elapsed_time(b) * 1e-3) / 1e9
+    out["note"] = ("register-only MFMA loops (4 independent accumulators per wavefront, 8 "
+                   "wavefronts per compute unit) and a 1 GiB device copy: what the simplest "
+                   "possible kernels sustain on this chip; the shader clock is read inside the "
+                   "loop (cycle counter over the 100 MHz counter)")
+    return out
 
 
 def read_traffic(kernel_tag):
@@ -415,6 +426,18 @@ def main():
         assign()
     clocks = read_clocks()
     torch.cuda.synchronize()
+    # the same launch on constant data (all keys and all centroids the same vector): same
+    # instruction stream, far fewer operand bits toggling, so a higher clock under load
+    K_flat = torch.ones_like(w.K)
+    hat_flat = torch.full_like(mu_hat, 128.0 ** -0.5)
+
+    def assign_flat():
+        ck.ck_kmeans_assign(sh, K_flat, 0, cfg.N, hat_flat, 0, cfg.C, labels2)
+
+    for _ in range(3):
+        assign_flat()
+    a_flat = train_stats(assign_flat, 10 * reps)["mean"]
+    del K_flat, hat_flat
 
     # sparse attention alone (partial + merge kernels of one call)
     def attn():
@@ -460,8 +483,8 @@ def main():
         "clocks_during_assignment_train": clocks,
         "recalled_kv_GBps": db["kv"] / (decode_ms * 1e-3) / 1e9,
         "recalled_tokens_mean": db["mean_tokens"],
-        "roofline": {"kernel": "k_assign (bf16 MFMA assignment, one launch = one K-means "
-                               "iteration over all head-problems)",
+        "roofline": {"kernel": "k_assign_stream (bf16 MFMA assignment, centroid table in LDS; "
+                               "one launch = one K-means iteration over all head-problems)",
                      "bound": "mfma", "achieved": achieved_tflops, "peak": PEAK_BF16_MFMA_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved_tflops / PEAK_BF16_MFMA_TFLOPS,
                      "traffic": read_traffic("k_assign_" + cfg.name),
@@ -471,9 +494,16 @@ def main():
                      "launch_ms_avg_note": "average over a back-to-back train of launches between "
                                            "one HIP event pair; a pair around every single launch "
                                            "adds ~3 us of dispatch latency",
-                     "launch_ms_single_pair_avg": a_avg, "launch_ms_single_pair_min": a_min},
-        "roofline_decode": {"kernels": "ck_decode_step = k_score + k_attn_partial(fused select/"
-                                       "gather) + k_attn_merge",
+                     "launch_ms_single_pair_avg": a_avg, "launch_ms_single_pair_min": a_min,
+                     "launch_ms_avg_constant_data": a_flat,
+                     "constant_data_note": "the same launch with every key and every centroid "
+                                           "the same vector: identical instruction stream; the "
+                                           "difference is the clock the chip holds under matrix "
+                                           "load (see measured_peaks: random against constant "
+                                           "operands)"},
+        "roofline_decode": {"kernels": "ck_decode_step = one launch of k_attn (scoring, "
+                                       "selection, gather, attention; the last workgroup of a "
+                                       "head-problem merges its splits)",
                             "bound": "hbm", "achieved": db["total"] / (decode_ms * 1e-3) / 1e9,
                             "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                             "frac": db["total"] / (decode_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS,

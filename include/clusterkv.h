@@ -484,10 +484,19 @@ int ck_cached_decode_step(const ck_shape* sh, const void* q, const void* K_home,
  * runs on) over n_workgroups workgroups of 4 wavefronts, `iters` x 16 MFMAs per
  * wavefront.  *flops [host] receives the floating-point operations of the launch,
  * so that flops / elapsed time is the matrix throughput the chip sustains at its
- * real clocks.  sink [dev]: at least one float, never written in practice.
+ * real clocks.  operands [dev, 16-byte aligned] or NULL: 16384 bytes, for each of the
+ * 64 lanes 8 A fragments then 8 B fragments of 8 bf16 each, used in rotation; NULL
+ * uses small constants.  The clock the chip holds under matrix load depends on how many
+ * operand bits toggle, so random operands give the figure that bounds a kernel
+ * working on real keys, constants an upper one.  clocks [dev, 8-byte aligned] or
+ * NULL: two words written by the first workgroup, the shader-clock cycles and the
+ * ticks of the constant 100 MHz counter spent in its loop (their ratio x 100 MHz is
+ * the clock it ran at).  sink [dev]: at least one float, never written in practice.
+ * Errors: CK_EINVALID (n_workgroups outside [1, 65535], iters outside [1, 2^24],
+ *   sink or flops NULL), CK_EMISALIGNED, CK_EHIP.
  */
-int ck_probe_mfma_bf16(int32_t n_workgroups, int32_t iters, float* sink, double* flops,
-                       void* stream);
+int ck_probe_mfma_bf16(int32_t n_workgroups, int32_t iters, const void* operands,
+                       uint64_t* clocks, float* sink, double* flops, void* stream);
 
 #ifdef __cplusplus
 }

@@ -139,7 +139,7 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.ck_cached_decode_step.argtypes = [SH, P, P, P, P, P, P, P, I32, I32, CC, I32, F, P, P, P,
                                           P, P, P, P, SZ, P]
     lib.ck_probe_mfma_bf16.restype = ctypes.c_int
-    lib.ck_probe_mfma_bf16.argtypes = [I32, I32, P, ctypes.POINTER(ctypes.c_double), P]
+    lib.ck_probe_mfma_bf16.argtypes = [I32, I32, P, P, P, ctypes.POINTER(ctypes.c_double), P]
     _lib = lib
     return lib
 
@@ -448,12 +448,24 @@ def cached_decode_step(st, cache: ClusterCache, q, K_home, V_home):
     return st.out
 
 
-def ck_probe_mfma_bf16(n_workgroups: int, iters: int, sink) -> float:
-    """Enqueue the MFMA probe; returns the flops of the launch."""
+def _probe_operands(t):
+    if t is None:
+        return None
+    if t.numel() * t.element_size() < 16384:
+        raise ValueError("probe operands need 16384 bytes")
+    return _ptr(t)
+
+
+def ck_probe_mfma_bf16(n_workgroups: int, iters: int, sink, operands=None, clocks=None) -> float:
+    """Enqueue the MFMA probe; returns the flops of the launch.  operands: 16384 bytes
+    on the device (per lane 8 A then 8 B fragments) or None for constants; clocks: two
+    int64 on the device that receive shader cycles and 100 MHz ticks, or None."""
     lib = load_library()
     fl = ctypes.c_double(0.0)
-    _check(lib.ck_probe_mfma_bf16(n_workgroups, iters, _ptr(sink), ctypes.byref(fl),
-                                  _stream(sink)))
+    _check(lib.ck_probe_mfma_bf16(n_workgroups, iters,
+                                  _probe_operands(operands),
+                                  _ptr(clocks) if clocks is not None else None,
+                                  _ptr(sink), ctypes.byref(fl), _stream(sink)))
     return fl.value
 
 

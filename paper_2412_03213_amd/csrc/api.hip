@@ -748,15 +748,18 @@ int ck_cached_decode_step(const ck_shape* sh, const void* q, const void* K_home,
                     "attention launch");
 }
 
-int ck_probe_mfma_bf16(int32_t n_workgroups, int32_t iters, float* sink, double* flops,
-                       void* stream) {
+int ck_probe_mfma_bf16(int32_t n_workgroups, int32_t iters, const void* operands,
+                       uint64_t* clocks, float* sink, double* flops, void* stream) {
   if (n_workgroups < 1 || n_workgroups > 65535 || iters < 1 || iters > (1 << 24))
     return fail(CK_EINVALID, "n_workgroups=%d or iters=%d out of range", n_workgroups, iters);
   CK_REQUIRE_PTR(sink);
   if (!flops) return fail(CK_EINVALID, "flops is NULL");
+  if (operands && ((uintptr_t)operands & 15)) return fail(CK_EMISALIGNED, "operands not 16-byte aligned");
+  if (clocks && ((uintptr_t)clocks & 7)) return fail(CK_EMISALIGNED, "clocks not 8-byte aligned");
   // 4 wavefronts x 16 MFMAs per iteration x 2*32*32*16 flop
   *flops = (double)n_workgroups * 4.0 * 16.0 * iters * 32768.0;
-  return hip_result(ck::launch_probe_mfma(n_workgroups, iters, sink, (hipStream_t)stream),
+  return hip_result(ck::launch_probe_mfma(n_workgroups, iters, operands, (unsigned long long*)clocks,
+                                          sink, (hipStream_t)stream),
                     "MFMA probe launch");
 }
 

@@ -209,7 +209,8 @@ hipError_t launch_gather(const Dims& dm, const int32_t* sel_clusters,
                          const int32_t* n_sel_clusters, const int32_t* offsets,
                          const int32_t* sorted_idx, int budget, uint32_t flags,
                          int32_t* token_idx, int idx_stride, int32_t* n_tokens, hipStream_t st);
-hipError_t launch_probe_mfma(int n_workgroups, int iters, float* sink, hipStream_t st);
+hipError_t launch_probe_mfma(int n_workgroups, int iters, const void* operands,
+                             unsigned long long* clocks, float* sink, hipStream_t st);
 // cluster cache
 struct CacheArgs {
   const void *K_home, *V_home;                          // [HP, N_cap, D]

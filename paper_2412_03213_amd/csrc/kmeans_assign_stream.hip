@@ -76,24 +76,21 @@ __global__ __launch_bounds__(ST_WAVES * 64, 2) void k_assign_stream(
   // ---- the table into LDS (rows beyond c_count are zero), bias, histograms ----
   {
     const int n_seg = n_tiles * 32 * 16;                // 16-byte segments
-    constexpr int PER = ST_MAX_TILES * 32 * 16 / THREADS;   // 16 per thread, 8 at a time
-    for (int i0 = 0; i0 < PER; i0 += 8) {
-      if (tid + i0 * THREADS >= n_seg) break;           // uniform enough: whole tail is empty
-      uint4 stage[8];
+    constexpr int PER = ST_MAX_TILES * 32 * 16 / THREADS;   // 16 per thread, all in flight at once
+    uint4 stage[PER];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int seg = tid + (i0 + i) * THREADS;
-        const int r = seg >> 4;
-        stage[i] = make_uint4(0, 0, 0, 0);
-        if (seg < n_seg && r < c_count)
-          stage[i] = *reinterpret_cast<const uint4*>(Mhp + (int64_t)r * D + (seg & 15) * 8);
-      }
+    for (int i = 0; i < PER; ++i) {
+      const int seg = tid + i * THREADS;
+      const int r = seg >> 4;
+      stage[i] = make_uint4(0, 0, 0, 0);
+      if (seg < n_seg && r < c_count)
+        stage[i] = *reinterpret_cast<const uint4*>(Mhp + (int64_t)r * D + (seg & 15) * 8);
+    }
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int seg = tid + (i0 + i) * THREADS;
-        if (seg < n_seg)
-          *reinterpret_cast<uint4*>(&table[(seg >> 4) * LDS_ROW + (seg & 15) * 8]) = stage[i];
-      }
+    for (int i = 0; i < PER; ++i) {
+      const int seg = tid + i * THREADS;
+      if (seg < n_seg)
+        *reinterpret_cast<uint4*>(&table[(seg >> 4) * LDS_ROW + (seg & 15) * 8]) = stage[i];
     }
   }
   // the first keys are requested after the table: loads come back in the order they were
