@@ -23,6 +23,7 @@ if ROOT not in sys.path:
 
 PEAK_BF16_MFMA_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
 PEAK_HBM_GBPS = 8000.0             # MI355X HBM3E peak
+USE_GRAPHS = True                  # --no-graphs clears it
 
 
 def parse():
@@ -51,6 +52,13 @@ def parse():
                     help="skip the full-depth configuration (all 32 layers x 8 sequences as one "
                          "batch of 2048 head-problems, ~36 GiB of HBM): the decode workload "
                          "on which the HBM roofline fraction is meaningful")
+    ap.add_argument("--counter-legs", action="store_true",
+                    help="launch each kernel of the timed workloads a few times and nothing else "
+                         "(no timing, no JSON figures): the run to put under rocprofv3 --pmc, "
+                         "which serialises dispatches and needs few of them")
+    ap.add_argument("--no-graphs", action="store_true",
+                    help="time the HIP-graph legs as plain launches instead (for runs under a "
+                         "counter-collecting profiler, which does not survive graph replays)")
     return ap.parse_args()
 
 
@@ -93,6 +101,10 @@ def read_clocks():
     the reason why not.  Called while a long train of kernels is queued on the GPU."""
     import re
     import subprocess
+    if any(k.startswith(("ROCPROF", "ROCP_")) for k in os.environ):
+        # under the profiler every child process loads its tool library, which touches the
+        # GPU before the SMI script starts its interpreter; do not start one there
+        return {"unavailable": "running under a profiler"}
     for cmd in (["/opt/rocm/bin/rocm-smi", "--showclocks"], ["rocm-smi", "--showclocks"]):
         try:
             out = subprocess.run(cmd, capture_output=True, text=True, timeout=20).stdout
@@ -262,10 +274,63 @@ def cpu_baseline_other_configs(budget_s=12.0):
     return out
 
 
+def counter_legs(cfg, w, st, sh, q, cluster, decode):
+    """A 1 GiB device copy (the calibration of the byte counters), then three launches of
+    every kernel of the 32k layer (clustering, the assignment alone, the decode step, the
+    attention alone) and of the batch-8 layer (64 head-problems, B = 2048)."""
+    import torch
+    import paper_2412_03213_amd as ck
+    from ck_synth import Config, MixtureWorkload, get_config, sample_init_indices
+    dev = "cuda:0"
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    for _ in range(2):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    del src, dst
+
+    def legs(cfg, w, st, sh, q, cluster, decode):
+        HP = cfg.S * cfg.Hkv
+        for _ in range(3):
+            cluster()
+        mu_hat = st.cluster_ws[:HP * cfg.C * cfg.d * 2].view(torch.bfloat16).view(
+            cfg.S, cfg.Hkv, cfg.C, cfg.d)
+        labels2 = torch.empty_like(st.labels)
+        for _ in range(3):
+            ck.ck_kmeans_assign(sh, w.K, 0, cfg.N, mu_hat, 0, cfg.C, labels2)
+        for _ in range(3):
+            decode()
+        for _ in range(3):
+            ck.ck_sparse_decode_attn(sh, q, w.K, w.V, st.token_idx, st.n_tokens, cfg.B, st.out,
+                                     workspace=st.attn_ws)
+        torch.cuda.synchronize()
+
+    legs(cfg, w, st, sh, q, cluster, decode)
+    c2 = get_config(2)
+    cfg8 = Config("batch8_layer", 1, c2.S, c2.Hkv, c2.Hq, c2.d, c2.N, c2.M, c2.C, c2.n_iter, c2.B,
+                  c2.seed)
+    w8 = MixtureWorkload(cfg8, device=dev)
+    w8.token_center = None
+    init8 = sample_init_indices(w8.K, cfg8.C, cfg8.seed).to(dev)
+    sh8 = ck.Shape(cfg8.S, cfg8.Hq, cfg8.Hkv, cfg8.N, cfg8.C)
+    st8 = ck.ClusterState(sh8, dev, budget=cfg8.B)
+    q8 = w8.query()
+
+    def cluster8():
+        st8.n_clusters = 0
+        st8.cluster(w8.K, init8, 0, cfg8.N, cfg8.C, cfg8.n_iter)
+
+    legs(cfg8, w8, st8, sh8, q8, cluster8, lambda: ck.decode_step(st8, q8, w8.K, w8.V))
+    print(json.dumps({"counter_legs": "done", "workloads": [cfg.name, "batch-8 layer (64 "
+                      "head-problems, N=32768, C=400, B=2048)"]}))
+
+
 def graph_ms(fn, reps, per_graph=1):
     """`per_graph` consecutive calls of fn (the layers of a model run one after another)
     captured into one HIP graph; average time per call over `reps` replays."""
     import torch
+    if not USE_GRAPHS:
+        return event_ms(fn, reps)
     one = fn
 
     def fn():
@@ -334,21 +399,24 @@ def measured_peaks(dev):
     return out
 
 
-def read_traffic(kernel_tag):
-    """HBM bytes per launch of a kernel as measured with rocprofv3 --pmc
+def read_traffic(kernel, workload):
+    """HBM bytes per launch of a kernel on a workload as measured with rocprofv3 --pmc
     (FETCH_SIZE + WRITE_SIZE, calibrated), from the committed summary if present."""
-    path = os.path.join(ROOT, "profiles", f"{kernel_tag}_pmc.md")
+    path = os.path.join(ROOT, "profiles", "k_assign_stream_and_k_attn_pmc.md")
+    tag = f"traffic_bytes_per_launch[{kernel}, {workload}]:"
     try:
         for line in open(path):
-            if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":")[1])
+            if line.startswith(tag):
+                return float(line[len(tag):])
     except OSError:
         pass
     return None
 
 
 def main():
+    global USE_GRAPHS
     args = parse()
+    USE_GRAPHS = not args.no_graphs
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (head-problems are independent; "
               "no multi-GPU path exists) -- rerun with --gpus 1", file=sys.stderr)
@@ -384,6 +452,9 @@ def main():
         cluster()
         decode()
 
+    if args.counter_legs:
+        counter_legs(cfg, w, st, sh, q, cluster, decode)
+        return
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -507,9 +578,12 @@ def main():
                             "bound": "hbm", "achieved": db["total"] / (decode_ms * 1e-3) / 1e9,
                             "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                             "frac": db["total"] / (decode_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS,
-                            "bytes_per_step": db["total"], "attn_call_us_avg": at_avg * 1e3,
+                            "bytes_per_step": db["total"],
+                            "traffic": read_traffic("k_attn", cfg.name),
+                            "attn_call_us_avg": at_avg * 1e3,
                             "attn_GBps": db["attn"] / (at_avg * 1e-3) / 1e9,
-                            "note": "batch 1: 8 head-problems, launch-latency bound"},
+                            "note": "batch 1: 8 head-problems, latency bound (a chain of "
+                                    "dependent memory round trips, 5 MB per step)"},
     }
 
     result["full_kv_decode"] = {
@@ -937,6 +1011,12 @@ def graph_seq_ms(fns, reps):
     into ONE HIP graph; average time per call over `reps` replays, plus median and
     minimum over the replays."""
     import torch
+    if not USE_GRAPHS:
+        def all_calls():
+            for f in fns:
+                f()
+        st = train_stats(all_calls, reps)
+        return {k: st[k] / len(fns) for k in ("mean", "median", "min")}
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):
@@ -1015,7 +1095,8 @@ def big_decode(reps, layers):
            "recalled_kv_GBps": db["kv"] / (best * 1e-3) / 1e9,
            "recalled_tokens_mean": db["mean_tokens"],
            "roofline": {"bound": "hbm", "achieved": gbps, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-                        "frac": gbps / PEAK_HBM_GBPS},
+                        "frac": gbps / PEAK_HBM_GBPS,
+                        "traffic": read_traffic("k_attn", "batch8_layer") if layers == 1 else None},
            "attn_call_us_avg": at_avg * 1e3, "attn_call_us_min": at_min * 1e3,
            "attn_GBps": db["attn"] / (at_avg * 1e-3) / 1e9,
            "kmeans_ms": t_cluster,
