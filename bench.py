@@ -540,6 +540,7 @@ def main():
                    "N": cfg.N, "C": cfg.C, "kmeans_iters": cfg.n_iter, "B": cfg.B,
                    "mixture_centers": cfg.M, "selection": "whole clusters"},
         "kmeans_keys_per_s": keys_per_step / (cluster_ms * 1e-3),
+        "kmeans_key_assignments_per_s": keys_per_step * cfg.n_iter / (cluster_ms * 1e-3),
         "kmeans_ms": cluster_ms, "kmeans_ms_median": cluster_st["median"],
         "kmeans_ms_min": cluster_st["min"],
         "decode_us_per_layer": decode_ms * 1e3,
