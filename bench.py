@@ -559,7 +559,7 @@ def main():
                                "one launch = one K-means iteration over all head-problems)",
                      "bound": "mfma", "achieved": achieved_tflops, "peak": PEAK_BF16_MFMA_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved_tflops / PEAK_BF16_MFMA_TFLOPS,
-                     "traffic": read_traffic("k_assign_" + cfg.name),
+                     "traffic": read_traffic("k_assign_stream", cfg.name),
                      "flops_per_launch": assign_flops,
                      "launch_ms_avg": a_train, "launch_ms_median": a_st["median"],
                      "launch_ms_min": a_st["min"],
