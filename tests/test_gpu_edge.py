@@ -21,11 +21,15 @@ def bf16_dev(a):
 
 
 @pytest.mark.parametrize("N,C,Hkv", [(1000, 1, 1), (300, 300, 1), (70001, 64, 1), (1537, 33, 3),
-                                     (2048, 2048, 1)])
+                                     (2048, 2048, 1), (5000, 512, 1), (5000, 513, 1),
+                                     (40000, 500, 2), (70, 5, 1)])
 def test_cluster_keys_shapes(N, C, Hkv):
     """C = 1 (global mean), C = N (every token its own cluster), a token count that is
     not a multiple of either assignment tile (512 for large problems, 128 for small),
-    the largest supported cluster count."""
+    the largest supported cluster count; the largest table the streaming assignment
+    kernel keeps in LDS (512 rows), one row more (the chunk-streaming kernel), a ragged
+    last tile at full LDS occupancy with several blocks per workgroup, and fewer tokens
+    than one 64-key task."""
     cfg = Config("edge", 1, 1, Hkv, Hkv, 128, N, max(4, min(C, 64)), C, 3, 64, seed=N % 97)
     w = MixtureWorkload(cfg, device=DEV)
     init = sample_init_indices(w.K, C, cfg.seed)
