@@ -164,10 +164,10 @@ def bf16_dev(a):
 
 
 def test_assignment_many_head_problems_all_keys_teacher_forced():
-    """The launch shape of the full-depth and batch-16 configurations (more 1024-token
-    tiles than compute units, C < 1024: four-wavefront workgroups, two per CU): every key
-    of three head-problems against the oracle's labels, given the oracle's own unit
-    centroids of its second iteration."""
+    """The launch shape of the full-depth and batch-16 configurations (64 head-problems,
+    C = 400: the streaming kernel with the table in LDS, several 512-token blocks per
+    workgroup): every key of three head-problems against the oracle's labels, given the
+    oracle's own unit centroids of its second iteration."""
     c2 = get_config(2)
     cfg = Config("assign_64hp", 1, c2.S, c2.Hkv, c2.Hq, c2.d, c2.N, c2.M, c2.C, 2, c2.B, 202)
     assert cfg.S * cfg.Hkv == 64 and cfg.N == 32768 and cfg.C == 400
@@ -201,13 +201,47 @@ def test_assignment_many_head_problems_all_keys_teacher_forced():
     assert int(lab[1, 1].max()) == 0 and int(lab[1, 1].min()) == 0
 
 
-@pytest.mark.parametrize("S,Hkv", [(1, 2), (2, 8)])
-def test_l2_assignment_large_tiles_all_keys(S, Hkv):
-    """The l2 metric (bias -|mu|^2/2 added in the assignment read-out) on the 512-token
-    assignment tiles: 2 head-problems take the eight-wavefront workgroups, 16 the
-    four-wavefront ones.  One iteration from the given initial rows is a teacher-forced
+@pytest.mark.parametrize("C", [600, 1100])
+def test_assignment_chunk_streaming_kernel_all_keys_teacher_forced(C):
+    """Tables of more than 512 centroids take the kernel that streams the table through
+    LDS in chunks: with 16 head-problems of 32768 tokens (more 1024-token tiles than
+    compute units) C = 600 runs its four-wavefront form, C = 1100 the eight-wavefront one.
+    Every key of two head-problems against the oracle, given unit centroids made from
+    sampled key rows."""
+    S, Hkv, N = 2, 8, 32768
+    cfg = Config("assign_chunks", 1, S, Hkv, Hkv, 128, N, 1024, C, 1, 256, seed=400 + C)
+    w = MixtureWorkload(cfg, device=DEV)
+    init = sample_init_indices(w.K, C, cfg.seed)
+    sh = ck.Shape(S, Hkv, Hkv, N, C)
+    picks = [(0, 1), (1, 6)]
+    hat = torch.zeros(S, Hkv, C, 128, dtype=torch.bfloat16, device=DEV)
+    tables = {}
+    for s, h in picks:
+        mu_hat = O.round_to_bf16(O.unit_rows(np64(w.K[s, h])[init[s, h].numpy()]))
+        tables[s, h] = mu_hat
+        hat[s, h] = bf16_dev(mu_hat)
+    lab = torch.full((S, Hkv, N), -1, dtype=torch.int32, device=DEV)
+    ck.ck_kmeans_assign(sh, w.K, 0, N, hat, 0, C, lab)
+    torch.cuda.synchronize()
+    flagged = 0
+    for s, h in picks:
+        lo, _, gap = O.assign(np64(w.K[s, h]), tables[s, h])
+        near = gap < 1e-4
+        bad = (lab[s, h].cpu().numpy() != lo) & ~near
+        assert not bad.any(), f"C={C} head-problem {(s, h)}: {bad.sum()} mismatches off near-ties"
+        flagged += int(near.sum())
+    assert flagged < 0.01 * len(picks) * N
+    print(f"assignment, C={C}, 16 head-problems: near-tie keys {flagged}/{len(picks) * N}")
+
+
+@pytest.mark.parametrize("S,Hkv,C", [(1, 2, 200), (2, 8, 200), (1, 2, 600), (2, 8, 600)])
+def test_l2_assignment_large_tiles_all_keys(S, Hkv, C):
+    """The l2 metric (bias -|mu|^2/2 added in the assignment read-out) at 32768 tokens per
+    head-problem: C = 200 takes the streaming kernel (table in LDS), C = 600 the
+    chunk-streaming one, with 2 head-problems in its eight-wavefront form and with 16 in
+    its four-wavefront form.  One iteration from the given initial rows is a teacher-forced
     assignment: the labels must be the oracle's nearest stored centroid off near-ties."""
-    N, C = 32768, 200
+    N = 32768
     cfg = Config("l2_big", 1, S, Hkv, Hkv, 128, N, 256, C, 1, 256, seed=31 + S)
     w = MixtureWorkload(cfg, device=DEV)
     init = sample_init_indices(w.K, C, cfg.seed)
