@@ -272,19 +272,20 @@ hipError_t launch_metadata(const Dims& dm, const int32_t* labels, int64_t tok_be
 
 // ------------------------------------------------------------------ update
 // One workgroup per cluster.  A 16-lane group reads one member row per step
-// (16 B per lane), 16 rows per workgroup step, four steps in flight.  Partial
-// sums are combined in a fixed order: lane groups of a wavefront, then the four
+// (16 B per lane), 4 rows per wavefront step, UPD_UNR steps in flight.  Partial
+// sums are combined in a fixed order: lane groups of a wavefront, then the
 // wavefronts through LDS.
-constexpr int UPD_THREADS = 256;
-__global__ __launch_bounds__(UPD_THREADS) void k_update(
+template <int UPD_WAVES, int UPD_UNR>
+__global__ __launch_bounds__(UPD_WAVES * 64) void k_update(
     const bf16* __restrict__ K, int64_t N_cap, int C_cap, const int32_t* __restrict__ offsets,
     const int32_t* __restrict__ sorted_idx, int c_begin, int c_count,
     bf16* __restrict__ centroids, bf16* __restrict__ mu_hat, float* __restrict__ centroids_f32,
     int metric, float* __restrict__ bias, int bias_stride, const int32_t* __restrict__ gate) {
-  __shared__ float part[4][D];
+  constexpr int GROUPS = UPD_WAVES * 4;                 // 16-lane groups: member rows per step
+  __shared__ float part[UPD_WAVES][D];
   const int c = blockIdx.x, hp = blockIdx.y, tid = threadIdx.x;
   if (gate && gate[hp] == 0) return;
-  const int lane = tid & 63, wave = tid >> 6, l16 = tid & 15, grp = tid >> 4;  // 16 groups
+  const int lane = tid & 63, wave = tid >> 6, l16 = tid & 15, grp = tid >> 4;
   const int32_t* off = offsets + (int64_t)hp * (C_cap + 1) + c_begin + c;
   const int beg = off[0], n = off[1] - beg;
   if (n <= 0) return;                                   // empty cluster keeps its centroid
@@ -294,11 +295,11 @@ __global__ __launch_bounds__(UPD_THREADS) void k_update(
   float acc[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) acc[j] = 0.f;
-  for (int j0 = 0; j0 < n; j0 += 64) {
-    uint4 w[4];
+  for (int j0 = 0; j0 < n; j0 += GROUPS * UPD_UNR) {
+    uint4 w[UPD_UNR];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int j = j0 + u * 16 + grp;
+    for (int u = 0; u < UPD_UNR; ++u) {
+      const int j = j0 + u * GROUPS + grp;
       if (j < n) {
         int64_t row = idx[j];
         row = row < 0 ? 0 : (row >= N_cap ? N_cap - 1 : row);
@@ -308,7 +309,7 @@ __global__ __launch_bounds__(UPD_THREADS) void k_update(
       }
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < UPD_UNR; ++u) {
       acc[0] += lo_bf16(w[u].x); acc[1] += hi_bf16(w[u].x);
       acc[2] += lo_bf16(w[u].y); acc[3] += hi_bf16(w[u].y);
       acc[4] += lo_bf16(w[u].z); acc[5] += hi_bf16(w[u].z);
@@ -329,9 +330,12 @@ __global__ __launch_bounds__(UPD_THREADS) void k_update(
   if (tid < 64) {
     // lane handles channels 2*lane, 2*lane+1
     const float inv_n = 1.0f / (float)n;
-    float m0 = ((part[0][2 * lane] + part[1][2 * lane]) + part[2][2 * lane]) + part[3][2 * lane];
-    float m1 = ((part[0][2 * lane + 1] + part[1][2 * lane + 1]) + part[2][2 * lane + 1]) +
-               part[3][2 * lane + 1];
+    float m0 = part[0][2 * lane], m1 = part[0][2 * lane + 1];
+#pragma unroll
+    for (int wv = 1; wv < UPD_WAVES; ++wv) {
+      m0 += part[wv][2 * lane];
+      m1 += part[wv][2 * lane + 1];
+    }
     m0 *= inv_n;
     m1 *= inv_n;
     const float n2 = wave_sum(m0 * m0 + m1 * m1);
@@ -360,7 +364,9 @@ hipError_t launch_update(const Dims& dm, const bf16* K, const int32_t* offsets,
                          const int32_t* sorted_idx, int c_begin, int c_count, bf16* centroids,
                          bf16* mu_hat, float* centroids_f32, int metric, float* bias,
                          int bias_stride, const int32_t* gate, hipStream_t st) {
-  hipLaunchKernelGGL(k_update, dim3(c_count, dm.HP), dim3(UPD_THREADS), 0, st, K, dm.N_cap,
+  // four wavefronts, eight rows in flight per 16-lane group: measured best of
+  // {1, 2, 4 wavefronts} x {4, 8, 16 in flight} (the summation order does not depend on it)
+  hipLaunchKernelGGL((k_update<4, 8>), dim3(c_count, dm.HP), dim3(4 * 64), 0, st, K, dm.N_cap,
                      dm.C_cap, offsets, sorted_idx, c_begin, c_count, centroids, mu_hat,
                      centroids_f32, metric, bias, bias_stride, gate);
   return hipGetLastError();
