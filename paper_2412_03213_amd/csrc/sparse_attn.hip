@@ -421,22 +421,22 @@ __global__ __launch_bounds__(ATT_THREADS) void k_attn(const AttnArgs a) {
           for (int j = 0; j < 8; ++j) acc[g][j] = fmaf(pr[u][g], vv[j], acc[g][j]);
       }
     };
-    // three register sets in rotation: the loads of steps t + 1 and t + 2 are in flight
-    // while step t is reduced
-    Regs ra, rb, rc;
+    // NS register sets in rotation: the loads of steps t + 1 .. t + NS - 1 are in flight
+    // while step t is reduced (4 and 6 sets were measured: no faster, the row stream is
+    // bound by memory bandwidth, not by the depth of the prefetch)
+    constexpr int NS = 3;
+    Regs rs[NS];
     constexpr int ST = ATT_STEP_TOKENS;
-    if (n_pos > 0) fetch(0, ra);
-    if (n_pos > ST) fetch(ST, rb);
-    for (int i0 = 0; i0 < n_pos; i0 += 3 * ST) {
-      if (i0 + 2 * ST < n_pos) fetch(i0 + 2 * ST, rc);
-      reduce(i0, ra);
-      if (i0 + ST < n_pos) {
-        if (i0 + 3 * ST < n_pos) fetch(i0 + 3 * ST, ra);
-        reduce(i0 + ST, rb);
-      }
-      if (i0 + 2 * ST < n_pos) {
-        if (i0 + 4 * ST < n_pos) fetch(i0 + 4 * ST, rb);
-        reduce(i0 + 2 * ST, rc);
+#pragma unroll
+    for (int j = 0; j < NS - 1; ++j)
+      if (j * ST < n_pos) fetch(j * ST, rs[j]);
+    for (int i0 = 0; i0 < n_pos; i0 += NS * ST) {
+#pragma unroll
+      for (int j = 0; j < NS; ++j) {
+        if (i0 + j * ST < n_pos) {
+          if (i0 + (j + NS - 1) * ST < n_pos) fetch(i0 + (j + NS - 1) * ST, rs[(j + NS - 1) % NS]);
+          reduce(i0 + j * ST, rs[j]);
+        }
       }
     }
     // ---- combine the 4 slots of a wavefront: they share the running max ----
