@@ -80,23 +80,31 @@ __global__ __launch_bounds__(ST_WAVES * 64, 2) void k_assign_stream(
     const int n_seg = n_tiles * 32 * 16;                // 16-byte segments
     constexpr int PER = ST_MAX_TILES * 32 * 16 / THREADS;   // 16 per thread, all in flight at once
     uint4 stage[PER];
+    // every load is unconditional (rows beyond the table re-read its last row and are
+    // replaced by zeros when they are written to LDS): a load under a branch makes the
+    // compiler wait for it before it issues the next one
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
       const int seg = tid + i * THREADS;
-      const int r = seg >> 4;
-      stage[i] = make_uint4(0, 0, 0, 0);
-      if (seg < n_seg && r < c_count)
-        stage[i] = *reinterpret_cast<const uint4*>(Mhp + (int64_t)r * D + (seg & 15) * 8);
+      int r = seg >> 4;
+      r = r < c_count ? r : c_count - 1;
+      stage[i] = *reinterpret_cast<const uint4*>(Mhp + (int64_t)r * D + (seg & 15) * 8);
     }
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
       const int seg = tid + i * THREADS;
+      const bool real = (seg >> 4) < c_count;
+      uint4 v = stage[i];
+      v.x = real ? v.x : 0u; v.y = real ? v.y : 0u; v.z = real ? v.z : 0u; v.w = real ? v.w : 0u;
       if (seg < n_seg)
-        *reinterpret_cast<uint4*>(&table[(seg >> 4) * LDS_ROW + (seg & 15) * 8]) = stage[i];
+        *reinterpret_cast<uint4*>(&table[(seg >> 4) * LDS_ROW + (seg & 15) * 8]) = v;
     }
   }
-  // the first keys are requested after the table: loads come back in the order they were
-  // issued, and the table (mostly out of L2) must not wait behind 32 MB of keys from HBM
+  // the first keys are requested after the table has arrived: loads come back in the
+  // order they were issued and share the memory system's bandwidth, and every earlier
+  // placement of this request that was tried (before the table, between its loads and
+  // its LDS writes, for half of the wavefronts only) delayed the table by more than it
+  // advanced the keys
   load_keys(wave, ka);
   if constexpr (HAS_BIAS) {
     for (int c = tid; c < n_tiles * 32; c += THREADS)
