@@ -186,6 +186,17 @@ __global__ __launch_bounds__(SORT_THREADS) void k_sort_scatter(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hp = blockIdx.y;
   if (gate && gate[hp] == 0) return;
   const int chunk = blockIdx.x;
+  // this thread's labels are requested first, unconditionally (a token beyond the range
+  // re-reads token 0), so that they travel while the offsets are being prepared
+  const int per_wave = chunk_tokens / 4;
+  const int32_t* lab = labels + (int64_t)hp * N_cap + tok_begin;
+  int lraw[SCAT_ROUNDS];
+#pragma unroll
+  for (int r = 0; r < SCAT_ROUNDS; ++r) {
+    const int in_wave = r * WAVE + lane;
+    const int64_t t = (int64_t)chunk * chunk_tokens + wave * per_wave + in_wave;
+    lraw[r] = lab[(in_wave < per_wave && t < tok_count) ? t : 0];
+  }
   int* offs = lds_hist;
   int* cnt = lds_hist + c_count;
   int32_t* off_g = offsets + (int64_t)hp * (C_cap + 1);
@@ -214,8 +225,6 @@ __global__ __launch_bounds__(SORT_THREADS) void k_sort_scatter(
   for (int i = tid; i < 4 * c_count; i += SORT_THREADS) cnt[i] = 0;
   __syncthreads();
 
-  const int per_wave = chunk_tokens / 4;
-  const int32_t* lab = labels + (int64_t)hp * N_cap + tok_begin;
   const uint64_t lt = ((uint64_t)1 << lane) - 1;
   volatile int* mine = cnt + wave * c_count;
   int lbl[SCAT_ROUNDS], rank[SCAT_ROUNDS];
@@ -225,7 +234,7 @@ __global__ __launch_bounds__(SORT_THREADS) void k_sort_scatter(
     const int in_wave = r * WAVE + lane;
     const int64_t t = (int64_t)chunk * chunk_tokens + wave * per_wave + in_wave;
     const bool valid = in_wave < per_wave && t < tok_count;
-    int l = valid ? lab[t] - c_begin : 0;
+    int l = valid ? lraw[r] - c_begin : 0;
     l = l < 0 ? 0 : (l >= c_count ? c_count - 1 : l);
     const uint64_t peers = same_label_mask(l, valid, label_bits);
     const int before = mine[l];
