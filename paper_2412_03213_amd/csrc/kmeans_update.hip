@@ -305,24 +305,31 @@ __global__ __launch_bounds__(UPD_WAVES * 64) void k_update(
 #pragma unroll
   for (int j = 0; j < 8; ++j) acc[j] = 0.f;
   for (int j0 = 0; j0 < n; j0 += GROUPS * UPD_UNR) {
-    uint4 w[UPD_UNR];
+    // two round trips per pass: all member ids, then all member rows.  Every load is
+    // unconditional (an entry beyond the cluster re-reads its last member and is
+    // replaced by zeros): a load under a branch makes the compiler wait for it, and for
+    // everything requested before it, ahead of the next one.
+    int64_t row[UPD_UNR];
 #pragma unroll
     for (int u = 0; u < UPD_UNR; ++u) {
       const int j = j0 + u * GROUPS + grp;
-      if (j < n) {
-        int64_t row = idx[j];
-        row = row < 0 ? 0 : (row >= N_cap ? N_cap - 1 : row);
-        w[u] = *reinterpret_cast<const uint4*>(Khp + row * D);
-      } else {
-        w[u] = make_uint4(0, 0, 0, 0);
-      }
+      row[u] = idx[j < n ? j : n - 1];
+    }
+    uint4 w[UPD_UNR];
+#pragma unroll
+    for (int u = 0; u < UPD_UNR; ++u) {
+      const int64_t r = row[u] < 0 ? 0 : (row[u] >= N_cap ? N_cap - 1 : row[u]);
+      w[u] = *reinterpret_cast<const uint4*>(Khp + r * D);
     }
 #pragma unroll
     for (int u = 0; u < UPD_UNR; ++u) {
-      acc[0] += lo_bf16(w[u].x); acc[1] += hi_bf16(w[u].x);
-      acc[2] += lo_bf16(w[u].y); acc[3] += hi_bf16(w[u].y);
-      acc[4] += lo_bf16(w[u].z); acc[5] += hi_bf16(w[u].z);
-      acc[6] += lo_bf16(w[u].w); acc[7] += hi_bf16(w[u].w);
+      const bool real = j0 + u * GROUPS + grp < n;
+      const uint32_t x = real ? w[u].x : 0u, y = real ? w[u].y : 0u;
+      const uint32_t z = real ? w[u].z : 0u, q = real ? w[u].w : 0u;
+      acc[0] += lo_bf16(x); acc[1] += hi_bf16(x);
+      acc[2] += lo_bf16(y); acc[3] += hi_bf16(y);
+      acc[4] += lo_bf16(z); acc[5] += hi_bf16(z);
+      acc[6] += lo_bf16(q); acc[7] += hi_bf16(q);
     }
   }
   // groups of one wavefront
