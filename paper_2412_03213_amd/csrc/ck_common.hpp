@@ -244,7 +244,7 @@ size_t objective_workspace_bytes(const Dims& dm, int64_t tok_count);
 hipError_t launch_objective(const Dims& dm, const bf16* K, int64_t tok_begin, int64_t tok_count,
                             const bf16* table, int c_begin, int c_count, const int32_t* labels,
                             double* J, double* Dsum, void* workspace, hipStream_t st);
-int attn_num_splits(const Dims& dm, int64_t max_total, bool fused);
+int attn_num_splits(const Dims& dm, int64_t max_total);
 size_t attn_workspace_bytes(const Dims& dm, int64_t max_total);
 // address, on the current device, of the library-owned scratch array
 // (CK_STATIC_SCRATCH_BYTES bytes); looked up once per device

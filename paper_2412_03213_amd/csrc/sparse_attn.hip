@@ -43,8 +43,7 @@ constexpr int ATT_STEP_TOKENS = 16 * ATT_UNROLL;   // 64 tokens per workgroup it
 constexpr int ATT_MAX_CHUNK = 2048;        // positions one workgroup may own (rows held in LDS)
 constexpr int ATT_MAX_SPLITS = 1024;       // workgroups per head-problem
 constexpr float NEG_BIG = -1.0e30f;        // "no token yet": finite so that differences stay finite
-constexpr int ATT_TARGET_WGS = 512;        // given index list: two per CU on 256 CUs
-constexpr int ATT_TARGET_WGS_FUSED = 256;  // selection inside: one per CU
+constexpr int ATT_TARGET_WGS = 256;        // one per CU on 256 CUs
 constexpr int PEX_WAVE = 16 * 8 + 8;       // floats of probability exchange per wavefront (G <= 8)
 constexpr int PART_STRIDE = D + 2;         // floats per (split, query head): max, sum, acc[128]
 constexpr int N_XCD = 8;                   // workgroup i of a launch runs on XCD i % 8
@@ -643,15 +642,16 @@ __global__ __launch_bounds__(D / 2) void k_attn_merge(const float* __restrict__ 
   store_out(out + (int64_t)hq_lin * D + c2 + 1, o2.y);
 }
 
-int attn_num_splits(const Dims& dm, int64_t max_total, bool fused) {
-  // With the index list given, aim for two workgroups per CU.  With scoring and
-  // selection inside, for one per CU (measured best of 64..1024 workgroups per launch at
-  // 8 to 128 head-problems: every split repeats the scoring and the selection, which
-  // costs more than the shorter token run saves).  Either way keep at least one full step
-  // of tokens per workgroup and never more positions than its LDS row table holds
+int attn_num_splits(const Dims& dm, int64_t max_total) {
+  // Aim for one workgroup per CU (measured best of 64..1024 workgroups per launch at 8 to
+  // 128 head-problems for the one-launch decode step: every split repeats the scoring and
+  // the selection, which costs more than the shorter token run saves; the attention over
+  // a given list would like twice as many at 64 head-problems, 17.1 against 18.5 us, but
+  // takes the same rule: the split boundaries fix the order of the fp32 sums, and all
+  // forms of the step must give the same bits).  Keep at least one full step of tokens
+  // per workgroup and never more positions than its LDS row table holds.
   const int64_t by_work = (max_total + ATT_STEP_TOKENS - 1) / ATT_STEP_TOKENS;
-  const int target = fused ? ATT_TARGET_WGS_FUSED : ATT_TARGET_WGS;
-  const int64_t by_fill = (target + dm.HP - 1) / dm.HP;
+  const int64_t by_fill = (ATT_TARGET_WGS + dm.HP - 1) / dm.HP;
   int64_t n = by_work < by_fill ? by_work : by_fill;
   if (n > 64) n = 64;
   const int64_t need = (max_total + ATT_MAX_CHUNK - 1) / ATT_MAX_CHUNK;
@@ -668,14 +668,13 @@ static size_t partial_bytes(const Dims& dm, int n_split) {
 size_t attn_workspace_bytes(const Dims& dm, int64_t max_total) {
   // split partials, then one 64-bit ticket word per head-problem
   const size_t t = ((size_t)dm.HP * sizeof(unsigned long long) + 255) & ~(size_t)255;
-  // sized for the form with more splits
-  return partial_bytes(dm, attn_num_splits(dm, max_total, false)) + t;
+  return partial_bytes(dm, attn_num_splits(dm, max_total)) + t;
 }
 
 template <typename T, int MODE, int CMAX>
 static hipError_t launch_attn_t(const Dims& dm, AttnArgs a, int64_t max_total, bool two_pass,
                                 hipStream_t st) {
-  const int n_split = attn_num_splits(dm, max_total, MODE != ATT_PLAIN);
+  const int n_split = attn_num_splits(dm, max_total);
   if (n_split > ATT_MAX_SPLITS) return hipErrorInvalidValue;
   int chunk = (int)((max_total + n_split - 1) / n_split);
   chunk = (chunk + ATT_STEP_TOKENS - 1) / ATT_STEP_TOKENS * ATT_STEP_TOKENS;

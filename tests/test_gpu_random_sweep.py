@@ -21,7 +21,7 @@ def np64(t):
     return t.detach().float().cpu().numpy().astype(np.float64)
 
 
-N_SEEDS = int(os.environ.get("CK_SWEEP_SEEDS", "24"))     # more seeds for a longer soak
+N_SEEDS = int(os.environ.get("CK_SWEEP_SEEDS", "300"))    # more seeds for a longer soak
 
 
 @pytest.mark.parametrize("seed", range(N_SEEDS))
