@@ -33,6 +33,8 @@ def test_random_shape(seed):
     N = int(rng.integers(40, 3000))
     n_sink = int(rng.choice([0, 0, 5, 16]))
     n_recent = int(rng.choice([0, 0, 7, 33]))
+    if N - n_sink - n_recent < 2:                         # always something to cluster
+        N = n_sink + n_recent + 2
     n_clu_tok = N - n_sink - n_recent
     C = int(rng.integers(1, min(n_clu_tok, 300) + 1))
     B = int(rng.integers(1, n_clu_tok + 50))
@@ -82,3 +84,44 @@ def test_random_shape(seed):
             else:
                 err = (np.abs(got - want).max(axis=-1) / np.abs(want).max(axis=-1)).max()
                 assert err <= 2e-2, err
+
+
+N_MID = int(os.environ.get("CK_SWEEP_MID_SEEDS", "6"))
+
+
+@pytest.mark.parametrize("seed", range(N_MID))
+def test_random_midsize_assignment(seed):
+    """Random mid-size clustering problems (thousands to tens of thousands of tokens, up to
+    24 head-problems, up to 700 clusters, cosine or l2), one iteration from the given
+    initial rows: a teacher-forced assignment in whatever kernel and launch shape the sizes
+    select (table in LDS with one or several blocks per workgroup, or the table streamed in
+    chunks).  Every key of two head-problems against the oracle, metadata exact."""
+    rng = np.random.default_rng(7000 + seed)
+    S = int(rng.integers(1, 4))
+    Hkv = int(rng.integers(1, 9))
+    N = int(rng.integers(3000, 60000))
+    C = int(rng.integers(2, 700))
+    l2 = bool(rng.integers(0, 2))
+    cfg = Config(f"m{seed}", 1, S, Hkv, Hkv, 128, N, max(2, C // 2), C, 1, 64, 900 + seed)
+    w = MixtureWorkload(cfg, device=DEV)
+    init = sample_init_indices(w.K, C, cfg.seed)
+    sh = ck.Shape(S, Hkv, Hkv, N, C)
+    st = ck.ClusterState(sh, DEV, budget=64)
+    st.cluster(w.K, init.to(DEV), 0, N, C, 1, flags=ck.CK_METRIC_L2 if l2 else 0)
+    torch.cuda.synchronize()
+    for s, h in {(0, 0), (S - 1, Hkv - 1)}:
+        keys = np64(w.K[s, h])
+        rows = keys[init[s, h].numpy()]
+        if l2:
+            lo, gap = O.assign_metric(keys, O.round_to_bf16(rows), O.L2)
+        else:
+            lo, _, gap = O.assign(keys, O.round_to_bf16(O.unit_rows(rows)))
+        got = st.labels[s, h].cpu().numpy()
+        near = gap < 1e-4
+        bad = (got != lo) & ~near
+        assert not bad.any(), f"seed {seed} S={S} Hkv={Hkv} N={N} C={C} l2={l2}: {bad.sum()} mismatches"
+        assert near.sum() < 0.02 * N
+        sizes, offs, sidx = O.build_metadata(got, C)
+        assert np.array_equal(st.sizes[s, h].cpu().numpy(), sizes)
+        assert np.array_equal(st.offsets[s, h].cpu().numpy(), offs)
+        assert np.array_equal(st.sorted_idx[s, h].cpu().numpy(), sidx)
