@@ -125,3 +125,67 @@ def test_random_midsize_assignment(seed):
         assert np.array_equal(st.sizes[s, h].cpu().numpy(), sizes)
         assert np.array_equal(st.offsets[s, h].cpu().numpy(), offs)
         assert np.array_equal(st.sorted_idx[s, h].cpu().numpy(), sidx)
+
+
+@pytest.mark.parametrize("seed", range(N_MID))
+def test_random_midsize_decode(seed):
+    """Random mid-size decode steps (up to 96 head-problems, contexts of thousands to tens
+    of thousands of tokens, up to 700 clusters, budgets up to 2048, both budget modes,
+    sinks and a recent window): the one-launch step against the three calls bit for bit
+    on every head-problem, and against the oracle on the GPU's own tables for three of
+    them.  Covers the split counts, the one-wavefront selection and its fallback, and
+    tables above 512 clusters (scores computed by a kernel of their own)."""
+    rng = np.random.default_rng(9000 + seed)
+    S = int(rng.integers(1, 13))
+    Hkv = int(rng.integers(1, 9))
+    G = int(rng.choice([1, 2, 4, 8]))
+    N = int(rng.integers(2000, 40000))
+    n_sink = int(rng.choice([0, 0, 16]))
+    n_recent = int(rng.choice([0, 0, 40, 319]))
+    n_clu_tok = N - n_sink - n_recent
+    C = int(rng.integers(2, 700))
+    B = int(rng.integers(16, 2049))
+    mode = int(rng.choice([ck.CK_SEL_WHOLE, ck.CK_SEL_TRIM_LAST]))
+    cfg = Config(f"d{seed}", 1, S, Hkv, Hkv * G, 128, N, max(2, C // 2), C, 2, B, 300 + seed)
+    w = MixtureWorkload(cfg, device=DEV)
+    sh = ck.Shape(S, Hkv * G, Hkv, N, C)
+    st = ck.ClusterState(sh, DEV, budget=B, max_recent=n_recent, n_sink=n_sink)
+    init = sample_init_indices(w.K, C, cfg.seed, n_sink, n_clu_tok)
+    st.cluster(w.K, init.to(DEV), n_sink, n_clu_tok, C, 2)
+    q = w.query()
+    rb, re = N - n_recent, N
+    out_f = ck.decode_step(st, q, w.K, w.V, flags=mode, n_sink=n_sink, recent_begin=rb,
+                           recent_end=re, fused=True).clone()
+    idx_f, n_f = st.token_idx.clone(), st.n_tokens.clone()
+    out_3 = ck.decode_step(st, q, w.K, w.V, flags=mode, n_sink=n_sink, recent_begin=rb,
+                           recent_end=re, fused=False).clone()
+    torch.cuda.synchronize()
+    what = f"seed {seed} S={S} Hkv={Hkv} G={G} N={N} C={C} B={B} mode={mode}"
+    assert torch.equal(out_f, out_3), what
+    assert torch.equal(n_f, st.n_tokens), what
+    for s in range(S):
+        for h in range(Hkv):
+            n = int(n_f[s, h])
+            assert torch.equal(idx_f[s, h, :n], st.token_idx[s, h, :n]), what
+    picks = {(0, 0), (S - 1, Hkv - 1), (S // 2, Hkv // 2)}
+    for s, h in picks:
+        n = int(n_f[s, h])
+        keys, vals = np64(w.K[s, h]), np64(w.V[s, h])
+        lab = st.labels[s, h, n_sink:n_sink + n_clu_tok].cpu().numpy()
+        sizes, offs, sidx = O.build_metadata(lab, C, tok_begin=n_sink)
+        assert np.array_equal(st.sizes[s, h].cpu().numpy(), sizes), what
+        assert np.array_equal(st.sorted_idx[s, h, :n_clu_tok].cpu().numpy(), sidx), what
+        mu = np64(st.centroids[s, h])
+        qg = np64(q[s, h * G:(h + 1) * G])
+        r = O.decode_step(qg, keys, vals, mu, sizes, offs, sidx, B, mode, n_sink, rb, re)
+        got_idx = idx_f[s, h, :n].cpu().numpy()
+        if not O.selection_near_tie(r["scores"], r["order"], r["n_sel"]):
+            assert np.array_equal(got_idx, r["idx"]), what
+        assert n <= B and (mode == ck.CK_SEL_WHOLE or n == min(B, n_clu_tok)), what
+        want = O.sparse_attention(qg, keys, vals, got_idx, n_sink, rb, re)
+        got = np64(out_f[s, h * G:(h + 1) * G])
+        if len(got_idx) + n_sink + n_recent == 0:           # nothing fits the budget: zeros
+            assert (got == 0).all(), what
+        else:
+            err = (np.abs(got - want).max(axis=-1) / np.abs(want).max(axis=-1)).max()
+            assert err <= 2e-2, (what, err)
