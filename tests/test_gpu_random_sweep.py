@@ -86,7 +86,7 @@ def test_random_shape(seed):
                 assert err <= 2e-2, err
 
 
-N_MID = int(os.environ.get("CK_SWEEP_MID_SEEDS", "6"))
+N_MID = int(os.environ.get("CK_SWEEP_MID_SEEDS", "12"))
 
 
 @pytest.mark.parametrize("seed", range(N_MID))
@@ -167,6 +167,17 @@ def test_random_midsize_decode(seed):
         for h in range(Hkv):
             n = int(n_f[s, h])
             assert torch.equal(idx_f[s, h, :n], st.token_idx[s, h, :n]), what
+    if mode == ck.CK_SEL_WHOLE and n_sink == 0 and n_recent == 0:
+        # the cached step (rows copied into a dense buffer first) gives the same bits; a
+        # cold cache misses every recalled token, the same query again none
+        cache = ck.ClusterCache(sh, DEV, cap_tokens=B)
+        ck.ck_cache_reset(sh, cache)
+        out_c = ck.cached_decode_step(st, cache, q, w.K, w.V).clone()
+        miss1 = cache.miss_tokens.clone()
+        out_c2 = ck.cached_decode_step(st, cache, q, w.K, w.V).clone()
+        torch.cuda.synchronize()
+        assert torch.equal(out_c, out_f) and torch.equal(out_c2, out_f), what
+        assert torch.equal(miss1, n_f) and int(cache.miss_tokens.sum()) == 0, what
     picks = {(0, 0), (S - 1, Hkv - 1), (S // 2, Hkv // 2)}
     for s, h in picks:
         n = int(n_f[s, h])
